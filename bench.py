@@ -1,0 +1,181 @@
+#!/usr/bin/env python3
+"""Benchmark of the PSKV hot path on one MI355X.
+
+A "step" is one pskv_attn_fwd call: the whole per-layer hot path (stack the suffix queries,
+prefix scores/values on the matrix cores, causal suffix part, online-softmax combine, store)
+over one batch of B synthetic candidates, with every tensor resident in HBM before timing.
+The default workload is the 8B-class GQA shape on which the throughput goal is stated.
+
+Prints ONE JSON line.  `value` = candidate suffixes per second per attention layer.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_F64_TFLOPS = 78.6        # MI355X fp64 vector
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def alg_counts(w, suf_len):
+    """Algorithmic work of one call: multiply-adds over visible keys only at 2 FLOP each, and
+    the bytes that must cross HBM once (valid Q rows in, valid O rows out, valid suffix K/V
+    rows in, prefix K/V once)."""
+    import numpy as np
+    l = suf_len.astype(np.int64)
+    e = 2 if w.dtype == "bf16" else 4
+    flops = int((w.Hq * 4 * w.D * (l * w.P + l * (l + 1) // 2)).sum())
+    exps = int((w.Hq * (l * w.P + l * (l + 1) // 2)).sum())
+    prefix_bytes = 2 * w.P * w.Hkv * w.D * e
+    bytes_ = int(l.sum()) * (2 * w.Hq + 2 * w.Hkv) * w.D * e + prefix_bytes
+    return flops, bytes_, prefix_bytes, exps
+
+
+def cpu_baseline(inp, budget_s=12.0):
+    """Time the CPU oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    from oracle import pskv_oracle as orc
+    w = inp.w
+    n = min(w.B, 8)
+    t_total, done = 0.0, 0
+    # grow the sample until roughly budget_s seconds of oracle time have been spent
+    while True:
+        sub = inp.take(np.arange(done, done + n))
+        t0 = time.perf_counter()
+        orc.attn(sub.q, sub.k_suf, sub.v_suf, sub.k_pre, sub.v_pre, sub.suf_len, sub.scale, w.dtype)
+        t_total += time.perf_counter() - t0
+        done += n
+        if t_total >= budget_s or done >= w.B:
+            break
+        rate = done / t_total
+        n = int(max(1, min(w.B - done, rate * (budget_s - t_total))))
+    return {"value": done / t_total, "unit": "candidates/s", "cores": orc.threads(), "kind": "oracle",
+            "sample": f"first {done} of {w.B} candidates of {w.name} (all heads), {t_total:.1f} s of oracle time"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="gqa8b_bf16")
+    ap.add_argument("--impl", default="auto")
+    ap.add_argument("--sets", type=int, default=0, help="rotating input/output buffer sets (0 = auto)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (the path needs no exchange between "
+              "candidates or KV heads; sharding is described in DESIGN.md). Use --gpus 1.",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2603_13420_amd import binding as pk, inputs as gen
+    import parity_util as pu
+
+    pk.load()
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    w = gen.WORKLOADS[args.workload]
+    inp = gen.make_inputs(w, pad="zero", workers=16)
+    flops, bytes_, prefix_bytes, exps = alg_counts(w, inp.suf_len)
+
+    # Rotating buffer sets so Q/K/V/O of consecutive calls do not sit in the 256 MB
+    # last-level cache: each set is a full copy of the suffix-side tensors and output.
+    e = 2 if w.dtype == "bf16" else 4
+    set_bytes = (2 * w.B * w.S * w.Hq + 2 * w.B * w.S * w.Hkv) * w.D * e
+    nsets = args.sets or int(max(2, min(8, (1 << 30) // max(1, set_bytes) + 1)))
+    base = pu.to_device(inp)
+    sets = []
+    for s in range(nsets):
+        d = base if s == 0 else {k: (v.clone() if k in ("q", "k_suf", "v_suf") else v) for k, v in base.items()}
+        d = dict(d, out=torch.empty_like(base["q"]))
+        sets.append(d)
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def call(d):
+        pk.pskv_attn_fwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"],
+                         out=d["out"], impl=args.impl, scale=inp.scale, stream=stream)
+
+    for i in range(args.warmup):
+        call(sets[i % nsets])
+    torch.cuda.synchronize()
+
+    # The timed region: exactly `steps` calls, wall clock bracketed by synchronisation, with
+    # HIP events on the launch stream for the kernel-only average.
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(args.steps):
+        call(sets[i % nsets])
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev_ms = ev0.elapsed_time(ev1) / args.steps
+    ms_per_step = wall * 1e3 / args.steps
+
+    # Per-launch kernel duration measured by the library itself with HIP events on the same
+    # stream (back-to-back launches, one buffer set per measurement, averaged over the sets).
+    per_set = [pk.pskv_attn_fwd_timed(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"],
+                                      d["suf_len"], d["out"], impl=args.impl, scale=inp.scale, iters=1,
+                                      stream=stream)
+               for _ in range(max(1, min(50, args.steps // nsets))) for d in sets]
+    kern_ms = float(np.mean(per_set))
+
+    # quick self-check of the timed configuration on a few candidates (not timed)
+    cand = np.array([0, w.B // 2, w.B - 1])
+    sub = inp.take(cand)
+    ref = pu.oracle_out(sub)
+    got = pu.out_to_f64(sets[0]["out"][torch.from_numpy(cand).to("cuda:0")])
+    chk = pu.compare(got, ref, sub.suf_len, w.dtype, "bench self-check")
+
+    cand_per_s = w.B / (ms_per_step * 1e-3)
+    if w.dtype == "bf16" and args.impl != "simple":
+        roof = {"bound": "mfma", "achieved": flops / (kern_ms * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s"}
+    elif w.dtype == "f32":
+        roof = {"bound": "alu", "achieved": flops / (kern_ms * 1e-3) / 1e12, "peak": PEAK_F64_TFLOPS,
+                "unit": "TFLOP/s"}
+    else:
+        roof = {"bound": "alu", "achieved": flops / (kern_ms * 1e-3) / 1e12, "peak": 157.3, "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel_ms"] = kern_ms
+    roof["alg_flops_per_launch"] = flops
+    hbm = {"bound": "hbm", "achieved": bytes_ / (kern_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+           "alg_bytes_per_launch": bytes_, "prefix_bytes_once": prefix_bytes}
+    hbm["frac"] = hbm["achieved"] / hbm["peak"]
+
+    line = {
+        "metric": "candidate suffixes/sec per attention layer", "value": cand_per_s, "unit": "candidates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == "bf16" and args.impl != "simple" else ("f64" if w.dtype == "f32" else "f32"),
+        "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "P": w.P, "S": w.S, "suffix_len": [w.len_lo, w.len_hi],
+                   "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "impl": args.impl, "buffer_sets": nsets,
+                   "seed": w.seed},
+        "achieved_tflops": flops / (ms_per_step * 1e-3) / 1e12,
+        "event_ms_per_step": ev_ms,
+        "roofline": roof, "roofline_hbm": hbm,
+        "exp_per_launch": exps,
+        "self_check": chk,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(inp)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,148 @@
+/*
+ * pskv.h - C ABI of the MI355X (gfx950) batched candidate-suffix attention library.
+ *
+ * The operation (paper Sec. 3 Eq. 2; Sec. 4.2 "prefix-shared, layer-wise lazy expansion";
+ * Sec. 4.3 "suffix-centric alignment"; App. F.5): B candidate suffixes, stored left-aligned
+ * and right-padded to S rows, attend (i) with full visibility to ONE shared prefix K/V of
+ * P rows that exists once in memory and is never expanded over the candidates, and
+ * (ii) causally to their own suffix K/V.  For candidate b, query row i < suf_len[b], query
+ * head h (KV head k = h / (Hq/Hkv)):
+ *
+ *     out[b,i,h,:] = softmax_j( scale * <q[b,i,h,:], Kvis_j> ) * Vvis_j ,
+ *     Kvis = k_pre[0..P-1,k,:] followed by k_suf[b,0..i,k,:]   (same for Vvis)
+ *
+ * which is exactly what a Standard KV cache (Eq. 3: prefix repeated B times) computes.
+ * Rows i >= suf_len[b] are written as 0 (lse: -inf); padded Q/K/V rows may hold anything,
+ * NaN included, and never influence a valid row.
+ *
+ * All pointers except the params struct and the returned strings are DEVICE pointers owned
+ * by the caller.  The library allocates, frees and retains no device memory and keeps no
+ * state between calls.  Work is enqueued on the given stream and the call returns without
+ * synchronising; suf_len is read on the device.  Inputs must not alias the outputs.
+ * No exception crosses this boundary: every failure is a status code, with a thread-local
+ * detail string available from pskv_last_error().  Validation happens on the host before
+ * anything is launched; a call that returns an error has launched nothing.
+ */
+#ifndef PSKV_H
+#define PSKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PSKV_OK = 0,
+    PSKV_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, Hq % Hkv != 0, misaligned pointer/stride */
+    PSKV_ERR_UNSUPPORTED = 2, /* shape or dtype outside what the kernels cover */
+    PSKV_ERR_WORKSPACE = 3,   /* workspace smaller than pskv_attn_fwd_workspace_bytes() */
+    PSKV_ERR_HIP = 4          /* the HIP runtime refused a launch or query */
+} pskv_status;
+
+typedef enum {
+    PSKV_DTYPE_F32 = 0, /* q/k/v/out are float; fp32 arithmetic throughout */
+    PSKV_DTYPE_BF16 = 1 /* q/k/v/out are bfloat16; bf16 MFMA with fp32 accumulation and fp32 softmax */
+} pskv_dtype;
+
+/* Kernel selection. AUTO picks the MFMA path whenever it covers the problem. */
+typedef enum {
+    PSKV_IMPL_AUTO = 0,
+    PSKV_IMPL_SIMPLE = 1, /* one wavefront per query row, fp32 vector arithmetic; any D <= 256, any dtype */
+    PSKV_IMPL_MFMA = 2    /* stacked-M bf16 MFMA path; bf16, D == 128 */
+} pskv_impl;
+
+/*
+ * Problem description.  Notation follows the paper: P = N_p (prefix length), S = padded
+ * suffix-side length (L_dec = N_s + N_t after padding), B = number of candidates
+ * (N_cand, the "expand factor" of App. F.2), Hkv KV heads shared by groups of Hq/Hkv
+ * consecutive query heads (GQA, App. C.1).
+ *
+ * Strides are in ELEMENTS; 0 means "contiguous" for the layouts
+ *     q, out: [B,S,Hq,D]     k_suf, v_suf: [B,S,Hkv,D]     k_pre, v_pre: [P,Hkv,D]
+ * and the innermost D dimension always has stride 1.  Non-zero strides must be multiples
+ * of 8 elements (bf16) / 4 elements (f32) so that every row stays 16-byte aligned.
+ */
+typedef struct {
+    int32_t B, S, P, Hq, Hkv, D; /* B,S,Hq,Hkv,D >= 1; P >= 0; Hq % Hkv == 0 */
+    int32_t dtype;               /* pskv_dtype */
+    int32_t impl;                /* pskv_impl */
+    float scale;                 /* softmax scale; <= 0 selects 1/sqrt(D) (Eq. 2) */
+    int32_t reserved;            /* must be 0 */
+    int64_t q_stride_b, q_stride_s, q_stride_h;
+    int64_t ks_stride_b, ks_stride_s, ks_stride_h; /* shared by k_suf and v_suf */
+    int64_t kp_stride_p, kp_stride_h;              /* shared by k_pre and v_pre */
+    int64_t o_stride_b, o_stride_s, o_stride_h;
+} pskv_attn_params;
+
+/* Library version as major*10000 + minor*100 + patch. Never fails. */
+int pskv_version(void);
+
+/* Static English name of a status code. Never NULL. */
+const char *pskv_status_str(pskv_status s);
+
+/* Detail text of the last error raised on the calling thread ("" if none). The pointer is
+ * valid until the next library call on the same thread. */
+const char *pskv_last_error(void);
+
+/*
+ * Device workspace, in bytes, that pskv_attn_fwd needs for this problem (0 when the chosen
+ * kernels are fully fused, which is the case for every path in this version).  Returns
+ * (size_t)-1 if the params are invalid.  Host-only, touches no device.
+ */
+size_t pskv_attn_fwd_workspace_bytes(const pskv_attn_params *p);
+
+/*
+ * Host-only check of a params struct (sizes, divisibility, dtype, strides, kernel coverage)
+ * with the same rules pskv_attn_fwd applies.  Touches no device.
+ */
+pskv_status pskv_attn_validate(const pskv_attn_params *p);
+
+/*
+ * Batched candidate-suffix attention, forward (the whole hot path of one attention layer:
+ * stacking of the B*S suffix queries into one dense row dimension, prefix scores and values
+ * on the matrix cores, per-candidate causal suffix attention, online-softmax combine,
+ * normalisation and store - Eq. 2 over the keys that App. F.5's concatenation would hold).
+ *
+ *   q       [B,S,Hq,D]   device, read-only
+ *   k_suf   [B,S,Hkv,D]  device, read-only      v_suf likewise
+ *   k_pre   [P,Hkv,D]    device, read-only, ONE copy for all candidates (may be NULL iff P == 0)
+ *   v_pre   likewise
+ *   suf_len [B] int32    device, values in [0,S]; NULL means every candidate has S rows.
+ *                        Values outside [0,S] are clamped on the device.
+ *   out     [B,S,Hq,D]   device, written in full (padded rows = 0)
+ *   lse     [B,Hq,S] f32 device or NULL: natural-log sum of exp of the scaled visible scores
+ *                        (-inf on padded rows)
+ *   workspace / workspace_bytes: device scratch of at least pskv_attn_fwd_workspace_bytes();
+ *                        may be NULL when that is 0
+ *   hip_stream           a hipStream_t passed as void*; NULL is the default stream
+ *
+ * All data pointers must be 16-byte aligned.  Returns PSKV_OK once the kernels are enqueued.
+ */
+pskv_status pskv_attn_fwd(const pskv_attn_params *p,
+                          const void *q, const void *k_suf, const void *v_suf,
+                          const void *k_pre, const void *v_pre,
+                          const int32_t *suf_len,
+                          void *out, float *lse,
+                          void *workspace, size_t workspace_bytes,
+                          void *hip_stream);
+
+/*
+ * Timing helper for benchmarks: enqueues `iters` back-to-back pskv_attn_fwd calls on
+ * `hip_stream`, bracketed by HIP events recorded on that same stream, waits for the last
+ * one and stores the mean duration of one call in *ms_per_call.  Arguments as for
+ * pskv_attn_fwd.  This call synchronises the stream.
+ */
+pskv_status pskv_attn_fwd_timed(const pskv_attn_params *p,
+                                const void *q, const void *k_suf, const void *v_suf,
+                                const void *k_pre, const void *v_pre,
+                                const int32_t *suf_len,
+                                void *out, float *lse,
+                                void *workspace, size_t workspace_bytes,
+                                void *hip_stream, int iters, float *ms_per_call);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PSKV_H */

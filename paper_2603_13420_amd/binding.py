@@ -1,0 +1,200 @@
+"""ctypes binding of libpskv.so: same names as include/pskv.h, argument marshalling only.
+
+Every step of the attention path runs inside the HIP library.  There is no fallback: if the
+library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libpskv.so")
+
+PSKV_OK, PSKV_ERR_INVALID_ARG, PSKV_ERR_UNSUPPORTED, PSKV_ERR_WORKSPACE, PSKV_ERR_HIP = range(5)
+PSKV_DTYPE_F32, PSKV_DTYPE_BF16 = 0, 1
+PSKV_IMPL_AUTO, PSKV_IMPL_SIMPLE, PSKV_IMPL_MFMA = 0, 1, 2
+_IMPL = {"auto": PSKV_IMPL_AUTO, "simple": PSKV_IMPL_SIMPLE, "mfma": PSKV_IMPL_MFMA}
+
+EXPORTS = ["pskv_version", "pskv_status_str", "pskv_last_error", "pskv_attn_fwd_workspace_bytes",
+           "pskv_attn_validate", "pskv_attn_fwd", "pskv_attn_fwd_timed"]
+
+
+class pskv_attn_params(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("B", "S", "P", "Hq", "Hkv", "D", "dtype", "impl")] + \
+               [("scale", ctypes.c_float), ("reserved", ctypes.c_int32)] + \
+               [(n, ctypes.c_int64) for n in (
+                   "q_stride_b", "q_stride_s", "q_stride_h",
+                   "ks_stride_b", "ks_stride_s", "ks_stride_h",
+                   "kp_stride_p", "kp_stride_h",
+                   "o_stride_b", "o_stride_s", "o_stride_h")]
+
+
+class PskvError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"pskv status {status} ({what})")
+        self.status = status
+
+
+_lib = None
+
+
+def load():
+    """Load the built library; raise if it is missing (no CPU or PyTorch fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
+                          "or `python -m paper_2603_13420_amd.build`")
+    lib = ctypes.CDLL(LIB_PATH)
+    P = ctypes.POINTER(pskv_attn_params)
+    vp = ctypes.c_void_p
+    lib.pskv_version.restype = ctypes.c_int
+    lib.pskv_status_str.restype = ctypes.c_char_p
+    lib.pskv_status_str.argtypes = [ctypes.c_int]
+    lib.pskv_last_error.restype = ctypes.c_char_p
+    lib.pskv_attn_fwd_workspace_bytes.restype = ctypes.c_size_t
+    lib.pskv_attn_fwd_workspace_bytes.argtypes = [P]
+    lib.pskv_attn_validate.restype = ctypes.c_int
+    lib.pskv_attn_validate.argtypes = [P]
+    fwd_args = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.pskv_attn_fwd.restype = ctypes.c_int
+    lib.pskv_attn_fwd.argtypes = fwd_args
+    lib.pskv_attn_fwd_timed.restype = ctypes.c_int
+    lib.pskv_attn_fwd_timed.argtypes = fwd_args + [ctypes.c_int, ctypes.POINTER(ctypes.c_float)]
+    _lib = lib
+    return lib
+
+
+def pskv_version() -> int:
+    return int(load().pskv_version())
+
+
+def pskv_status_str(status: int) -> str:
+    return load().pskv_status_str(int(status)).decode()
+
+
+def pskv_last_error() -> str:
+    return load().pskv_last_error().decode()
+
+
+def _raise(status: int):
+    raise PskvError(status, f"{pskv_status_str(status)}: {pskv_last_error()}")
+
+
+def make_params(B, S, P, Hq, Hkv, D, dtype: str, impl: str = "auto", scale: float = 0.0,
+                **strides) -> pskv_attn_params:
+    p = pskv_attn_params()
+    p.B, p.S, p.P, p.Hq, p.Hkv, p.D = B, S, P, Hq, Hkv, D
+    p.dtype = {"f32": PSKV_DTYPE_F32, "bf16": PSKV_DTYPE_BF16}[dtype]
+    p.impl = _IMPL[impl]
+    p.scale = scale
+    p.reserved = 0
+    for k, v in strides.items():
+        setattr(p, k, int(v))
+    return p
+
+
+def pskv_attn_validate(p: pskv_attn_params) -> int:
+    return int(load().pskv_attn_validate(ctypes.byref(p)))
+
+
+def pskv_attn_fwd_workspace_bytes(p: pskv_attn_params) -> int:
+    n = int(load().pskv_attn_fwd_workspace_bytes(ctypes.byref(p)))
+    if n == ctypes.c_size_t(-1).value:
+        _raise(pskv_attn_validate(p))
+    return n
+
+
+def _params_from_tensors(q, k_suf, k_pre, out, impl, scale):
+    import torch
+    B, S, Hq, D = q.shape
+    Hkv = k_suf.shape[2]
+    P = 0 if k_pre is None else k_pre.shape[0]
+    dtype = {torch.float32: "f32", torch.bfloat16: "bf16"}[q.dtype]
+    for t in (q, k_suf, out) + (() if k_pre is None else (k_pre,)):
+        if t.stride(-1) != 1:
+            raise ValueError("innermost dimension must have stride 1")
+    st = dict(q_stride_b=q.stride(0), q_stride_s=q.stride(1), q_stride_h=q.stride(2),
+              ks_stride_b=k_suf.stride(0), ks_stride_s=k_suf.stride(1), ks_stride_h=k_suf.stride(2),
+              o_stride_b=out.stride(0), o_stride_s=out.stride(1), o_stride_h=out.stride(2))
+    if k_pre is not None and P > 0:
+        st.update(kp_stride_p=k_pre.stride(0), kp_stride_h=k_pre.stride(1))
+    return make_params(B, S, P, Hq, Hkv, D, dtype, impl, scale, **st)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _check_inputs(q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse):
+    import torch
+    dev = q.device
+    if dev.type != "cuda":
+        raise ValueError("tensors must live on the GPU")
+    for name, t in (("k_suf", k_suf), ("v_suf", v_suf), ("k_pre", k_pre), ("v_pre", v_pre), ("out", out)):
+        if t is None:
+            continue
+        if t.device != dev or t.dtype != q.dtype:
+            raise ValueError(f"{name}: device/dtype differ from q")
+    B, S, Hq, D = q.shape
+    Hkv = k_suf.shape[2]
+    if tuple(k_suf.shape) != (B, S, Hkv, D) or tuple(v_suf.shape) != (B, S, Hkv, D):
+        raise ValueError("k_suf/v_suf must be [B,S,Hkv,D]")
+    if v_suf.stride() != k_suf.stride():
+        raise ValueError("k_suf and v_suf must share strides")
+    if k_pre is not None:
+        if tuple(k_pre.shape[1:]) != (Hkv, D) or tuple(v_pre.shape) != tuple(k_pre.shape):
+            raise ValueError("k_pre/v_pre must be [P,Hkv,D]")
+        if v_pre.stride() != k_pre.stride():
+            raise ValueError("k_pre and v_pre must share strides")
+    if tuple(out.shape) != (B, S, Hq, D):
+        raise ValueError("out must be [B,S,Hq,D]")
+    if suf_len is not None and (suf_len.dtype != torch.int32 or tuple(suf_len.shape) != (B,)
+                                or not suf_len.is_contiguous() or suf_len.device != dev):
+        raise ValueError("suf_len must be a contiguous int32 [B] tensor on the same device")
+    if lse is not None and (lse.dtype != torch.float32 or tuple(lse.shape) != (B, Hq, S)
+                            or not lse.is_contiguous() or lse.device != dev):
+        raise ValueError("lse must be a contiguous float32 [B,Hq,S] tensor on the same device")
+
+
+def pskv_attn_fwd(q, k_suf, v_suf, k_pre, v_pre, suf_len=None, out=None, lse=None,
+                  impl: str = "auto", scale: float = 0.0, stream: Optional[int] = None):
+    """Enqueue one forward call on torch's current stream (or `stream`, a raw hipStream_t).
+    `out` (and `lse`) are allocated by torch when not given; returns `out`."""
+    import torch
+    if out is None:
+        out = torch.empty_like(q)
+    _check_inputs(q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse)
+    p = _params_from_tensors(q, k_suf, k_pre, out, impl, scale)
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    with torch.cuda.device(q.device):
+        rc = load().pskv_attn_fwd(ctypes.byref(p), _ptr(q), _ptr(k_suf), _ptr(v_suf), _ptr(k_pre),
+                                  _ptr(v_pre), _ptr(suf_len), _ptr(out), _ptr(lse), None, 0,
+                                  ctypes.c_void_p(stream))
+    if rc != PSKV_OK:
+        _raise(rc)
+    return out
+
+
+def pskv_attn_fwd_timed(q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse=None, impl: str = "auto",
+                        scale: float = 0.0, iters: int = 10, stream: Optional[int] = None) -> float:
+    """Mean milliseconds of one call over `iters` back-to-back calls, measured with HIP events
+    on the stream the kernels run on.  Synchronises that stream."""
+    import torch
+    _check_inputs(q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse)
+    p = _params_from_tensors(q, k_suf, k_pre, out, impl, scale)
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    ms = ctypes.c_float(0.0)
+    with torch.cuda.device(q.device):
+        rc = load().pskv_attn_fwd_timed(ctypes.byref(p), _ptr(q), _ptr(k_suf), _ptr(v_suf),
+                                        _ptr(k_pre), _ptr(v_pre), _ptr(suf_len), _ptr(out),
+                                        _ptr(lse), None, 0, ctypes.c_void_p(stream), int(iters),
+                                        ctypes.byref(ms))
+    if rc != PSKV_OK:
+        _raise(rc)
+    return float(ms.value)

@@ -1,0 +1,203 @@
+// Host side of the C ABI declared in include/pskv.h: argument validation, kernel choice,
+// launches on the caller's stream.  No device memory is allocated here.
+#include "../../include/pskv.h"
+#include "pskv_internal.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+pskv_status fail(pskv_status s, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return s;
+}
+
+constexpr size_t kSimpleMaxLds = 64 * 1024;
+
+// Fills `a` (without pointers) and `use_mfma` from p, applying every host-side rule.
+pskv_status resolve(const pskv_attn_params *p, pskv::Args &a, bool &use_mfma)
+{
+    if (!p)
+        return fail(PSKV_ERR_INVALID_ARG, "params is NULL");
+    if (p->B < 1 || p->S < 1 || p->Hq < 1 || p->Hkv < 1 || p->D < 1 || p->P < 0)
+        return fail(PSKV_ERR_INVALID_ARG, "sizes must satisfy B,S,Hq,Hkv,D >= 1 and P >= 0 (got B=%d S=%d P=%d Hq=%d Hkv=%d D=%d)",
+                    p->B, p->S, p->P, p->Hq, p->Hkv, p->D);
+    if (p->Hq % p->Hkv != 0)
+        return fail(PSKV_ERR_INVALID_ARG, "Hq=%d is not a multiple of Hkv=%d", p->Hq, p->Hkv);
+    if (p->reserved != 0)
+        return fail(PSKV_ERR_INVALID_ARG, "reserved field must be 0");
+    if (p->dtype != PSKV_DTYPE_F32 && p->dtype != PSKV_DTYPE_BF16)
+        return fail(PSKV_ERR_INVALID_ARG, "unknown dtype %d", p->dtype);
+    if (p->impl != PSKV_IMPL_AUTO && p->impl != PSKV_IMPL_SIMPLE && p->impl != PSKV_IMPL_MFMA)
+        return fail(PSKV_ERR_INVALID_ARG, "unknown impl %d", p->impl);
+    if (!(p->scale == p->scale) || std::isinf(p->scale))
+        return fail(PSKV_ERR_INVALID_ARG, "scale is not finite");
+    const int vec = p->dtype == PSKV_DTYPE_BF16 ? 8 : 4; // elements per 16 bytes
+    if (p->D % vec != 0)
+        return fail(PSKV_ERR_UNSUPPORTED, "D=%d must be a multiple of %d so rows stay 16-byte aligned", p->D, vec);
+    if (p->D > 256)
+        return fail(PSKV_ERR_UNSUPPORTED, "D=%d exceeds the supported maximum of 256", p->D);
+    const long long rows = (long long)p->B * p->S * p->Hq;
+    if (rows > 0x7fffffffLL)
+        return fail(PSKV_ERR_UNSUPPORTED, "B*S*Hq=%lld exceeds 2^31-1", rows);
+
+    a.B = p->B; a.S = p->S; a.P = p->P; a.Hq = p->Hq; a.Hkv = p->Hkv; a.D = p->D;
+    a.G = p->Hq / p->Hkv;
+    a.scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)p->D);
+
+    struct { const char *name; long long given, dflt; long long *dst; } st[] = {
+        {"q_stride_h", p->q_stride_h, (long long)p->D, &a.q_sh},
+        {"q_stride_s", p->q_stride_s, (long long)p->Hq * p->D, &a.q_ss},
+        {"q_stride_b", p->q_stride_b, (long long)p->S * p->Hq * p->D, &a.q_sb},
+        {"ks_stride_h", p->ks_stride_h, (long long)p->D, &a.ks_sh},
+        {"ks_stride_s", p->ks_stride_s, (long long)p->Hkv * p->D, &a.ks_ss},
+        {"ks_stride_b", p->ks_stride_b, (long long)p->S * p->Hkv * p->D, &a.ks_sb},
+        {"kp_stride_h", p->kp_stride_h, (long long)p->D, &a.kp_sh},
+        {"kp_stride_p", p->kp_stride_p, (long long)p->Hkv * p->D, &a.kp_sp},
+        {"o_stride_h", p->o_stride_h, (long long)p->D, &a.o_sh},
+        {"o_stride_s", p->o_stride_s, (long long)p->Hq * p->D, &a.o_ss},
+        {"o_stride_b", p->o_stride_b, (long long)p->S * p->Hq * p->D, &a.o_sb},
+    };
+    for (auto &s : st) {
+        if (s.given < 0)
+            return fail(PSKV_ERR_INVALID_ARG, "%s=%lld is negative", s.name, s.given);
+        if (s.given != 0 && s.given % vec != 0)
+            return fail(PSKV_ERR_INVALID_ARG, "%s=%lld is not a multiple of %d elements (16 bytes)", s.name, s.given, vec);
+        if (s.given != 0 && s.given < p->D)
+            return fail(PSKV_ERR_INVALID_ARG, "%s=%lld is smaller than D=%d (rows would overlap)", s.name, s.given, p->D);
+        *s.dst = s.given ? s.given : s.dflt;
+    }
+
+    const bool mfma_ok = pskv::mfma_supported(a, p->dtype);
+    if (p->impl == PSKV_IMPL_MFMA && !mfma_ok)
+        return fail(PSKV_ERR_UNSUPPORTED, "the MFMA path needs dtype bf16 and D == 128 (got dtype=%d D=%d S=%d)",
+                    p->dtype, p->D, p->S);
+    use_mfma = mfma_ok && p->impl != PSKV_IMPL_SIMPLE;
+    if (!use_mfma && pskv::simple_lds_bytes(a, p->dtype) > kSimpleMaxLds)
+        return fail(PSKV_ERR_UNSUPPORTED, "the simple path keeps one score row in LDS: P+S+D=%d is too large",
+                    p->P + p->S + p->D);
+    return PSKV_OK;
+}
+
+bool misaligned(const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) != 0; }
+
+} // namespace
+
+extern "C" {
+
+int pskv_version(void) { return 100; }
+
+const char *pskv_status_str(pskv_status s)
+{
+    switch (s) {
+    case PSKV_OK: return "ok";
+    case PSKV_ERR_INVALID_ARG: return "invalid argument";
+    case PSKV_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+    case PSKV_ERR_WORKSPACE: return "workspace too small";
+    case PSKV_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+const char *pskv_last_error(void) { return g_err; }
+
+size_t pskv_attn_fwd_workspace_bytes(const pskv_attn_params *p)
+{
+    pskv::Args a{};
+    bool use_mfma = false;
+    if (resolve(p, a, use_mfma) != PSKV_OK)
+        return (size_t)-1;
+    return 0; // every path is fully fused
+}
+
+pskv_status pskv_attn_validate(const pskv_attn_params *p)
+{
+    pskv::Args a{};
+    bool use_mfma = false;
+    pskv_status s = resolve(p, a, use_mfma);
+    if (s == PSKV_OK)
+        g_err[0] = '\0';
+    return s;
+}
+
+pskv_status pskv_attn_fwd(const pskv_attn_params *p, const void *q, const void *k_suf,
+                          const void *v_suf, const void *k_pre, const void *v_pre,
+                          const int32_t *suf_len, void *out, float *lse, void *workspace,
+                          size_t workspace_bytes, void *hip_stream)
+{
+    (void)workspace;
+    (void)workspace_bytes; // no path needs scratch
+    pskv::Args a{};
+    bool use_mfma = false;
+    pskv_status s = resolve(p, a, use_mfma);
+    if (s != PSKV_OK)
+        return s;
+    if (!q || !k_suf || !v_suf || !out)
+        return fail(PSKV_ERR_INVALID_ARG, "q, k_suf, v_suf and out must not be NULL");
+    if (a.P > 0 && (!k_pre || !v_pre))
+        return fail(PSKV_ERR_INVALID_ARG, "k_pre and v_pre must not be NULL when P > 0");
+    const void *ptrs[] = {q, k_suf, v_suf, k_pre, v_pre, out};
+    for (const void *ptr : ptrs)
+        if (misaligned(ptr))
+            return fail(PSKV_ERR_INVALID_ARG, "data pointer %p is not 16-byte aligned", ptr);
+    if ((reinterpret_cast<uintptr_t>(suf_len) & 3u) || (reinterpret_cast<uintptr_t>(lse) & 3u))
+        return fail(PSKV_ERR_INVALID_ARG, "suf_len and lse must be 4-byte aligned");
+    if (out == q || out == k_suf || out == v_suf || out == k_pre || out == v_pre)
+        return fail(PSKV_ERR_INVALID_ARG, "out must not alias an input");
+
+    a.q = q; a.ks = k_suf; a.vs = v_suf; a.kp = k_pre; a.vp = v_pre;
+    a.len = suf_len; a.out = out; a.lse = lse;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = use_mfma ? pskv::launch_mfma(a, stream) : pskv::launch_simple(a, p->dtype, stream);
+    if (e != hipSuccess)
+        return fail(PSKV_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+    g_err[0] = '\0';
+    return PSKV_OK;
+}
+
+pskv_status pskv_attn_fwd_timed(const pskv_attn_params *p, const void *q, const void *k_suf,
+                                const void *v_suf, const void *k_pre, const void *v_pre,
+                                const int32_t *suf_len, void *out, float *lse, void *workspace,
+                                size_t workspace_bytes, void *hip_stream, int iters,
+                                float *ms_per_call)
+{
+    if (iters < 1 || !ms_per_call)
+        return fail(PSKV_ERR_INVALID_ARG, "iters must be >= 1 and ms_per_call non-NULL");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipEvent_t t0 = nullptr, t1 = nullptr;
+    if (hipEventCreate(&t0) != hipSuccess || hipEventCreate(&t1) != hipSuccess) {
+        if (t0) (void)hipEventDestroy(t0);
+        return fail(PSKV_ERR_HIP, "hipEventCreate failed");
+    }
+    pskv_status s = PSKV_OK;
+    hipError_t e = hipEventRecord(t0, stream);
+    for (int it = 0; it < iters && s == PSKV_OK && e == hipSuccess; ++it)
+        s = pskv_attn_fwd(p, q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse, workspace,
+                          workspace_bytes, hip_stream);
+    if (e == hipSuccess)
+        e = hipEventRecord(t1, stream);
+    if (e == hipSuccess)
+        e = hipEventSynchronize(t1);
+    float ms = 0.f;
+    if (e == hipSuccess)
+        e = hipEventElapsedTime(&ms, t0, t1);
+    (void)hipEventDestroy(t0);
+    (void)hipEventDestroy(t1);
+    if (s != PSKV_OK)
+        return s;
+    if (e != hipSuccess)
+        return fail(PSKV_ERR_HIP, "event timing failed: %s", hipGetErrorString(e));
+    *ms_per_call = ms / (float)iters;
+    return PSKV_OK;
+}
+
+} // extern "C"

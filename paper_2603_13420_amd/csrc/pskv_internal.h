@@ -1,0 +1,34 @@
+// Internal declarations shared by the host entry points and the kernel translation units.
+// Nothing in here is part of the public ABI (that is include/pskv.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pskv {
+
+// A fully resolved problem: every stride filled in (elements), scale resolved, pointers typed
+// by the launcher. Passed to kernels by value.
+struct Args {
+    int B, S, P, Hq, Hkv, D, G;
+    float scale;
+    const void *q, *ks, *vs, *kp, *vp;
+    const int *len; // may be null: every candidate has S rows
+    void *out;
+    float *lse; // may be null
+    long long q_sb, q_ss, q_sh;
+    long long ks_sb, ks_ss, ks_sh;
+    long long kp_sp, kp_sh;
+    long long o_sb, o_ss, o_sh;
+};
+
+// Simple path: one wavefront per query row. dtype 0 = f32 storage (fp64 arithmetic),
+// 1 = bf16 storage (fp32 arithmetic). Returns the HIP launch status.
+hipError_t launch_simple(const Args &a, int dtype, hipStream_t stream);
+// Largest dynamic LDS the simple path needs for this problem, in bytes.
+size_t simple_lds_bytes(const Args &a, int dtype);
+
+// MFMA path: bf16, D == 128.
+bool mfma_supported(const Args &a, int dtype);
+hipError_t launch_mfma(const Args &a, hipStream_t stream);
+
+} // namespace pskv

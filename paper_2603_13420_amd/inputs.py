@@ -152,7 +152,8 @@ def make_inputs(w: Workload, pad: str = "nan", seed: Optional[int] = None,
 
     with ThreadPoolExecutor(max_workers=max(1, workers)) as ex:
         list(ex.map(block, range(nblk)))
-    scale = 1.0 / float(np.sqrt(w.D))
+    # the softmax scale 1/sqrt(D) as the fp32 number the C ABI carries; the same value goes to both sides
+    scale = float(np.float32(1.0 / np.sqrt(w.D)))
     return Inputs(w, q, k_suf, v_suf, k_pre, v_pre, suf_len, scale, {"pad": pad})
 
 

@@ -1,0 +1,117 @@
+"""CPU-side checks of the C ABI: the library loads, exports what include/pskv.h declares,
+and rejects bad problems on the host before anything could be launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2603_13420_amd import binding as pk
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "pskv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pskv_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = pk.load()
+    names = declared_functions()
+    assert set(names) == set(pk.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert pk.pskv_version() >= 100
+    for s in range(5):
+        assert pk.pskv_status_str(s) not in ("", "unknown status")
+
+
+def test_params_struct_matches_header_layout():
+    # 10 four-byte fields then 11 eight-byte strides, no padding surprises
+    assert ctypes.sizeof(pk.pskv_attn_params) == 10 * 4 + 11 * 8
+    assert pk.pskv_attn_params.q_stride_b.offset == 40
+
+
+def ok(**kw):
+    base = dict(B=8, S=16, P=48, Hq=4, Hkv=4, D=64, dtype="f32")
+    base.update(kw)
+    return pk.make_params(**base)
+
+
+def test_valid_problems_pass_on_host():
+    assert pk.pskv_attn_validate(ok()) == pk.PSKV_OK
+    assert pk.pskv_attn_fwd_workspace_bytes(ok()) == 0
+    assert pk.pskv_attn_validate(ok(P=0)) == pk.PSKV_OK
+    assert pk.pskv_attn_validate(ok(B=1024, S=24, P=256, Hq=32, Hkv=8, D=128, dtype="bf16")) == pk.PSKV_OK
+    assert pk.pskv_attn_validate(ok(Hq=28, Hkv=4, D=128, dtype="bf16")) == pk.PSKV_OK
+    assert pk.pskv_attn_validate(ok(D=128, dtype="bf16", impl="mfma")) == pk.PSKV_OK
+
+
+@pytest.mark.parametrize("kw,status,needle", [
+    (dict(B=0), pk.PSKV_ERR_INVALID_ARG, "sizes"),
+    (dict(S=0), pk.PSKV_ERR_INVALID_ARG, "sizes"),
+    (dict(P=-1), pk.PSKV_ERR_INVALID_ARG, "sizes"),
+    (dict(Hq=6, Hkv=4), pk.PSKV_ERR_INVALID_ARG, "multiple"),
+    (dict(D=66), pk.PSKV_ERR_UNSUPPORTED, "16-byte"),
+    (dict(D=512), pk.PSKV_ERR_UNSUPPORTED, "maximum"),
+    (dict(q_stride_h=-64), pk.PSKV_ERR_INVALID_ARG, "negative"),
+    (dict(q_stride_h=66), pk.PSKV_ERR_INVALID_ARG, "16 bytes"),
+    (dict(o_stride_s=32), pk.PSKV_ERR_INVALID_ARG, "overlap"),
+    (dict(scale=float("nan")), pk.PSKV_ERR_INVALID_ARG, "finite"),
+    (dict(impl="mfma"), pk.PSKV_ERR_UNSUPPORTED, "MFMA"),              # f32 has no MFMA path
+    (dict(D=64, dtype="bf16", impl="mfma"), pk.PSKV_ERR_UNSUPPORTED, "MFMA"),
+    (dict(P=40000, impl="simple"), pk.PSKV_ERR_UNSUPPORTED, "LDS"),
+])
+def test_bad_problems_are_refused_with_a_reason(kw, status, needle):
+    p = ok(**kw)
+    assert pk.pskv_attn_validate(p) == status
+    assert needle in pk.pskv_last_error()
+    with pytest.raises(pk.PskvError):
+        pk.pskv_attn_fwd_workspace_bytes(p)
+
+
+def test_unknown_enums_and_reserved():
+    p = ok()
+    p.dtype = 7
+    assert pk.pskv_attn_validate(p) == pk.PSKV_ERR_INVALID_ARG
+    p = ok()
+    p.impl = 9
+    assert pk.pskv_attn_validate(p) == pk.PSKV_ERR_INVALID_ARG
+    p = ok()
+    p.reserved = 1
+    assert pk.pskv_attn_validate(p) == pk.PSKV_ERR_INVALID_ARG
+    assert pk.load().pskv_attn_validate(None) == pk.PSKV_ERR_INVALID_ARG
+
+
+def test_fwd_refuses_null_and_misaligned_pointers_before_any_launch():
+    """Pointer checks run on the host before the first HIP call, so they are testable here."""
+    lib = pk.load()
+    p = ok()
+    null = ctypes.c_void_p(0)
+    a = ctypes.c_void_p(0x1000)
+    rc = lib.pskv_attn_fwd(ctypes.byref(p), null, a, a, a, a, None, a, None, None, 0, None)
+    assert rc == pk.PSKV_ERR_INVALID_ARG and "NULL" in pk.pskv_last_error()
+    rc = lib.pskv_attn_fwd(ctypes.byref(p), a, a, a, null, a, None, ctypes.c_void_p(0x2000), None, None, 0, None)
+    assert rc == pk.PSKV_ERR_INVALID_ARG and "k_pre" in pk.pskv_last_error()
+    rc = lib.pskv_attn_fwd(ctypes.byref(p), ctypes.c_void_p(0x1008), a, a, a, a, None,
+                           ctypes.c_void_p(0x2000), None, None, 0, None)
+    assert rc == pk.PSKV_ERR_INVALID_ARG and "aligned" in pk.pskv_last_error()
+    rc = lib.pskv_attn_fwd(ctypes.byref(p), a, a, a, a, a, None, a, None, None, 0, None)
+    assert rc == pk.PSKV_ERR_INVALID_ARG and "alias" in pk.pskv_last_error()
+    ms = ctypes.c_float()
+    rc = lib.pskv_attn_fwd_timed(ctypes.byref(p), a, a, a, a, a, None, ctypes.c_void_p(0x2000), None,
+                                 None, 0, None, 0, ctypes.byref(ms))
+    assert rc == pk.PSKV_ERR_INVALID_ARG
+
+
+def test_product_path_does_not_import_the_oracle():
+    """No file of the package imports, links or loads anything of the CPU oracle."""
+    pkg = os.path.join(ROOT, "paper_2603_13420_amd")
+    pat = re.compile(r"(import\s+oracle|from\s+oracle|pskv_oracle|oracle/|oracle\.)")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".cpp", ".hip", ".h")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert not pat.search(src), f

@@ -1,0 +1,183 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Padded rows are NaN-poisoned in every case."""
+import numpy as np
+import pytest
+
+from paper_2603_13420_amd import inputs as gen
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def pk():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2603_13420_amd import binding
+    binding.load()   # raises if the HIP library is missing: there is no fallback
+    return binding
+
+
+def run_case(pk, inp, impl, want_lse=True, what=""):
+    import torch
+    d = pu.to_device(inp)
+    w = inp.w
+    lse = torch.full((w.B, w.Hq, w.S), 123.0, device="cuda:0") if want_lse else None
+    out = torch.full_like(d["q"], float("nan"))
+    print(f"[case] {what or w.name} impl={impl} B={w.B} P={w.P} S={w.S} Hq={w.Hq} Hkv={w.Hkv} "
+          f"D={w.D} {w.dtype} seed={w.seed}", flush=True)
+    pk.pskv_attn_fwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"],
+                     out=out, lse=lse, impl=impl, scale=inp.scale)
+    torch.cuda.synchronize()
+    got = pu.out_to_f64(out)
+    if want_lse:
+        ref, ref_lse = pu.oracle_out(inp, want_lse=True)
+        pu.compare_lse(lse.cpu().numpy().astype(np.float64), ref_lse, inp.suf_len, w.dtype, what)
+    else:
+        ref = pu.oracle_out(inp)
+    res = pu.compare(got, ref, inp.suf_len, w.dtype, what or w.name)
+    print(f"       {res}", flush=True)
+    return res
+
+
+IMPLS_BF16 = ["simple", "mfma"]
+
+
+def test_tiny_f32_full(pk):
+    run_case(pk, gen.make_inputs(gen.WORKLOADS["tiny_f32"], pad="nan"), "auto")
+    run_case(pk, gen.make_inputs(gen.WORKLOADS["tiny_f32"], pad="nan"), "simple")
+
+
+@pytest.mark.parametrize("impl", IMPLS_BF16)
+@pytest.mark.parametrize("B,P,S,lo,hi,Hq,Hkv", [
+    (5, 48, 16, 1, 16, 4, 4),       # several row tiles of one candidate, ragged
+    (7, 100, 20, 20, 20, 8, 8),     # MHA, S not a multiple of 16, P not a multiple of 64
+    (6, 256, 24, 16, 24, 8, 2),     # GQA group 4, the headline shape in small
+    (3, 0, 24, 0, 24, 4, 1),        # no prefix at all: plain causal attention per candidate
+    (4, 17, 1, 0, 1, 4, 2),         # one-token suffixes, some empty
+    (3, 300, 33, 5, 33, 14, 2),     # group 7 (28/4-style), odd sizes everywhere
+    (2, 700, 70, 33, 70, 2, 2),     # suffix longer than one key tile
+    (1, 64, 16, 16, 16, 1, 1),      # single candidate, single head
+])
+def test_small_shapes_bf16(pk, impl, B, P, S, lo, hi, Hq, Hkv):
+    w = gen.custom_workload(f"small_{B}_{P}_{S}_{Hq}_{Hkv}", B, P, S, lo, hi, Hq, Hkv, 128, "bf16",
+                            index=200 + B + P)
+    run_case(pk, gen.make_inputs(w, pad="nan"), impl)
+
+
+@pytest.mark.parametrize("D", [32, 64, 256])
+def test_other_head_dims_simple(pk, D):
+    for dtype in ("f32", "bf16"):
+        w = gen.custom_workload(f"d{D}_{dtype}", 3, 21, 9, 0, 9, 6, 3, D, dtype, index=300 + D)
+        run_case(pk, gen.make_inputs(w, pad="nan"), "simple")
+
+
+@pytest.mark.parametrize("impl", ["simple", "mfma"])
+def test_suf_len_null_means_full_length(pk, impl):
+    import torch
+    w = gen.custom_workload("full", 4, 40, 12, 12, 12, 4, 2, 128, "bf16", index=400)
+    inp = gen.make_inputs(w, pad="nan")
+    d = pu.to_device(inp)
+    out = pk.pskv_attn_fwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], None, impl=impl, scale=inp.scale)
+    torch.cuda.synchronize()
+    pu.compare(pu.out_to_f64(out), pu.oracle_out(inp), inp.suf_len, "bf16", "suf_len=NULL")
+
+
+@pytest.mark.parametrize("impl", ["simple", "mfma"])
+def test_strided_views_of_a_fused_qkv_buffer(pk, impl):
+    """q, k, v as column slices of one [B,S,(Hq+2Hkv)*D] projection output, out with a
+    padded head stride: only strides change, the result must not."""
+    import torch
+    w = gen.custom_workload("strided", 5, 70, 18, 3, 18, 8, 2, 128, "bf16", index=401)
+    inp = gen.make_inputs(w, pad="nan")
+    d = pu.to_device(inp)
+    B, S, Hq, Hkv, D = w.B, w.S, w.Hq, w.Hkv, w.D
+    fused = torch.full((B, S, Hq + 2 * Hkv, D), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    fused[:, :, :Hq] = d["q"]
+    fused[:, :, Hq:Hq + Hkv] = d["k_suf"]
+    fused[:, :, Hq + Hkv:] = d["v_suf"]
+    kv_pre = torch.stack([d["k_pre"], d["v_pre"]], dim=2)       # [P,Hkv,2,D]
+    out_buf = torch.full((B, S, Hq, 2 * D), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    out = out_buf[..., :D]
+    pk.pskv_attn_fwd(fused[:, :, :Hq], fused[:, :, Hq:Hq + Hkv], fused[:, :, Hq + Hkv:],
+                     kv_pre[:, :, 0], kv_pre[:, :, 1], d["suf_len"], out=out, impl=impl, scale=inp.scale)
+    torch.cuda.synchronize()
+    pu.compare(pu.out_to_f64(out.contiguous()), pu.oracle_out(inp), inp.suf_len, "bf16", "strided")
+    assert torch.isnan(out_buf[..., D:]).all()      # nothing written outside the view
+
+
+def test_out_of_range_lengths_are_clamped(pk):
+    import torch
+    w = gen.custom_workload("clamp", 4, 30, 8, 8, 8, 2, 2, 128, "bf16", index=402)
+    inp = gen.make_inputs(w, pad="keep")
+    d = pu.to_device(inp)
+    weird = torch.tensor([-3, 8, 100, 0], dtype=torch.int32, device="cuda:0")
+    clamped = np.array([0, 8, 8, 0], dtype=np.int32)
+    ref = pu.oracle_out(gen.Inputs(inp.w, inp.q, inp.k_suf, inp.v_suf, inp.k_pre, inp.v_pre,
+                                   clamped, inp.scale))
+    for impl in ("simple", "mfma"):
+        out = pk.pskv_attn_fwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], weird, impl=impl, scale=inp.scale)
+        torch.cuda.synchronize()
+        pu.compare(pu.out_to_f64(out), ref, clamped, "bf16", f"clamp {impl}")
+
+
+def test_runs_on_a_side_stream_and_is_deterministic(pk):
+    import torch
+    w = gen.custom_workload("stream", 6, 128, 20, 20, 20, 8, 8, 128, "bf16", index=403)
+    inp = gen.make_inputs(w, pad="nan")
+    d = pu.to_device(inp)
+    ref = pu.oracle_out(inp)
+    side = torch.cuda.Stream()
+    outs = []
+    with torch.cuda.stream(side):
+        for _ in range(2):
+            outs.append(pk.pskv_attn_fwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"],
+                                         d["suf_len"], impl="auto", scale=inp.scale))
+    side.synchronize()
+    assert torch.equal(outs[0].view(torch.uint16), outs[1].view(torch.uint16))
+    pu.compare(pu.out_to_f64(outs[0]), ref, inp.suf_len, "bf16", "side stream")
+
+
+def test_mha7b_full_size_full_compare(pk):
+    """7B-class MHA shape at its full size, every output element compared."""
+    inp = gen.make_inputs(gen.WORKLOADS["mha7b_bf16"], pad="nan")
+    run_case(pk, inp, "auto")
+
+
+def test_gqa8b_full_size_full_compare(pk):
+    """8B-class GQA shape (the benchmark's configuration) at full size, every element."""
+    inp = gen.make_inputs(gen.WORKLOADS["gqa8b_bf16"], pad="nan")
+    run_case(pk, inp, "auto")
+
+
+def sampled_candidates(inp, n, rng):
+    """First/last candidates, extremes of the length mix, and a random remainder."""
+    B = inp.w.B
+    sl = inp.suf_len
+    picks = {0, 1, B - 2, B - 1, int(np.argmin(sl)), int(np.argmax(sl))}
+    picks |= set(int(x) for x in rng.choice(B, size=min(B, n), replace=False))
+    return np.array(sorted(picks))[:max(n, 6)]
+
+
+@pytest.mark.parametrize("name,nsample", [("longprefix_bf16", 24), ("mha13b_bf16", 48)])
+def test_large_shapes_full_size_sampled_compare(pk, name, nsample):
+    """Run at full size in the benchmark's launch configuration; the oracle recomputes a sample
+    of candidates one by one (a candidate depends only on the prefix and itself), and every
+    candidate is checked for finiteness and exact zeros on padding."""
+    import torch
+    inp = gen.make_inputs(gen.WORKLOADS[name], pad="nan", workers=16)
+    w = inp.w
+    print(f"[case] {name} full size, sampled compare", flush=True)
+    d = pu.to_device(inp)
+    out = pk.pskv_attn_fwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], impl="auto",
+                            scale=inp.scale)
+    torch.cuda.synchronize()
+    valid = (torch.arange(w.S, device="cuda:0")[None, :] < d["suf_len"][:, None])
+    assert torch.isfinite(out[valid].float()).all()
+    assert (out[~valid] == 0).all()
+    cand = sampled_candidates(inp, nsample, np.random.default_rng(1))
+    sub = inp.take(cand)
+    ref = pu.oracle_out(sub)
+    got = pu.out_to_f64(out[torch.from_numpy(cand).to("cuda:0")])
+    res = pu.compare(got, ref, sub.suf_len, "bf16", name)
+    print(f"       {len(cand)} candidates: {res}", flush=True)
