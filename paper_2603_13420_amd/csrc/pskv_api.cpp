@@ -52,6 +52,8 @@ pskv_status resolve(const pskv_attn_params *p, pskv::Args &a, bool &use_mfma)
 
     a.B = p->B; a.S = p->S; a.P = p->P; a.Hq = p->Hq; a.Hkv = p->Hkv; a.D = p->D;
     a.G = p->Hq / p->Hkv;
+    a.div_g = pskv::make_fastdiv((unsigned)a.G);
+    a.div_s = pskv::make_fastdiv((unsigned)a.S);
     a.scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)p->D);
 
     struct { const char *name; long long given, dflt; long long *dst; } st[] = {

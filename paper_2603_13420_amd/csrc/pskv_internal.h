@@ -8,8 +8,25 @@ namespace pskv {
 
 // A fully resolved problem: every stride filled in (elements), scale resolved, pointers typed
 // by the launcher. Passed to kernels by value.
+// Exact unsigned division by a runtime constant d for numerators below 2^31:
+// n / d == (n * mul) >> shift, with shift = 31 + ceil(log2 d) and mul = ceil(2^shift / d).
+struct FastDiv {
+    unsigned mul, shift;
+};
+inline FastDiv make_fastdiv(unsigned d)
+{
+    unsigned s = 0;
+    while ((1ull << s) < d)
+        ++s;
+    FastDiv f;
+    f.shift = 31 + s;
+    f.mul = (unsigned)(((1ull << f.shift) + d - 1) / d);
+    return f;
+}
+
 struct Args {
     int B, S, P, Hq, Hkv, D, G;
+    FastDiv div_g, div_s; // division by G and by S
     float scale;
     const void *q, *ks, *vs, *kp, *vp;
     const int *len; // may be null: every candidate has S rows
@@ -27,8 +44,12 @@ hipError_t launch_simple(const Args &a, int dtype, hipStream_t stream);
 // Largest dynamic LDS the simple path needs for this problem, in bytes.
 size_t simple_lds_bytes(const Args &a, int dtype);
 
-// MFMA path: bf16, D == 128.
+// MFMA path: bf16, D == 128.  Prefixes of up to 256 rows take the kernel that keeps the whole
+// prefix K/V of one head resident in LDS; longer ones are streamed through LDS in tiles.
 bool mfma_supported(const Args &a, int dtype);
 hipError_t launch_mfma(const Args &a, hipStream_t stream);
+bool resident_supported(const Args &a);
+hipError_t launch_resident(const Args &a, hipStream_t stream);
+hipError_t launch_stream(const Args &a, hipStream_t stream);
 
 } // namespace pskv

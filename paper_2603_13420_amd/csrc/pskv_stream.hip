@@ -414,6 +414,11 @@ bool mfma_supported(const Args &a, int dtype)
 
 hipError_t launch_mfma(const Args &a, hipStream_t stream)
 {
+    return resident_supported(a) ? launch_resident(a, stream) : launch_stream(a, stream);
+}
+
+hipError_t launch_stream(const Args &a, hipStream_t stream)
+{
     static bool attr_set = false; // raising the dynamic LDS limit is idempotent; a race is harmless
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(mfma_stream_kernel),
