@@ -146,6 +146,9 @@ __device__ inline void softmax_tile(const floatx16 &s, RowState &st, float c, bf
     }
 }
 
+// ALIGNED1: every 32-row block lies inside one candidate (S*G is a multiple of 32) and the
+// suffix fits one 32-key step (S <= 32).
+template <bool ALIGNED1>
 __global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
 void resident_kernel(Args a, int wgs_per_head, int ntiles)
 {
@@ -201,40 +204,114 @@ void resident_kernel(Args a, int wgs_per_head, int ntiles)
     const int sv_row_lo = 4 * ((sp5 >> 4) & 1) + ((sp5 >> 1) & 3); // + 8*(fragment & 1)
     const int sv_chunk_lo = 2 * ((sp5 >> 3) & 1) + (sp5 & 1);     // + 4*(fragment >> 1)
 
-    for (int blk = wg_in_head * kNW + wave; blk < nblocks; blk += wgs_per_head * kNW) {
-        const int r0 = blk * kBlockRows;
-        // ---- this lane's query row ----
-        const int r = r0 + c32;
-        const bool rin = r < Mtot;
-        const unsigned rr = rin ? r : Mtot - 1;
+    // Row bookkeeping of this lane for one block: candidate, suffix position, query head, and
+    // the (still unclamped) suffix length of that candidate.
+    struct Row {
+        unsigned rb, ri;
+        int rh, rlen;
+        bool rin;
+    };
+    auto decode = [&](int blk) {
+        Row x;
+        const int r = blk * kBlockRows + c32;
+        x.rin = r < Mtot;
+        const unsigned rr = x.rin ? r : Mtot - 1;
         const unsigned tok = fdiv(rr, a.div_g), gq = rr - tok * a.G;
-        const unsigned rb = fdiv(tok, a.div_s), ri = tok - rb * a.S;
-        int rlen = a.len ? a.len[rb] : a.S;
-        rlen = rlen < 0 ? 0 : (rlen > a.S ? a.S : rlen);
-        const bool rvalid = rin && (int)ri < rlen;
-        const int rh = head * a.G + gq;
-        unsigned short *orow = og + (long long)rb * a.o_sb + (long long)ri * a.o_ss + (long long)rh * a.o_sh;
-
-        if (__builtin_amdgcn_ballot_w64(rvalid) == 0) { // nothing but padding: defined as zero
-            if (rin) {
+        x.rb = fdiv(tok, a.div_s);
+        x.ri = tok - x.rb * a.S;
+        x.rh = head * a.G + gq;
+        x.rlen = a.len ? a.len[x.rb] : a.S;
+        return x;
+    };
+    // Q fragments of a block: lane (row c32, half h) holds d = 16*ks + 8*h ..+7 for ks = 0..7.
+    auto load_q = [&](const Row &x, uintx4 (&dst)[8]) {
+        const unsigned short *qrow =
+            qg + (long long)x.rb * a.q_sb + (long long)x.ri * a.q_ss + (long long)x.rh * a.q_sh + 8 * h;
 #pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    *reinterpret_cast<uintx4 *>(orow + 64 * h + 8 * u) = uintx4{0, 0, 0, 0};
-                if (a.lse && h == 0)
-                    a.lse[((long long)rb * a.Hq + rh) * a.S + ri] = -INFINITY;
-            }
-            continue;
-        }
+        for (int ks = 0; ks < 8; ++ks)
+            dst[ks] = ld_global16(qrow + 16 * ks);
+    };
+    // Wave-uniform clamped suffix length of candidate b (scalar load: it does not queue behind
+    // the vector loads in flight).
+    // (Read through the constant address space: suf_len is never written during the call.)
+    typedef const __attribute__((address_space(4))) int *const_int_ptr;
+    const const_int_ptr len_c = (const_int_ptr)(unsigned long long)a.len;
+    auto len_of = [&](int b) {
+        int len = a.len ? len_c[__builtin_amdgcn_readfirstlane(b)] : a.S;
+        return len < 0 ? 0 : (len > a.S ? a.S : len);
+    };
 
-        bf16x8 qf[8];
-        {
-            const unsigned short *qrow = qg + (long long)rb * a.q_sb + (long long)ri * a.q_ss + (long long)rh * a.q_sh;
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                uintx4 v = ld_global16(qrow + 16 * ks + 8 * h);
-                qf[ks] = as_bf16x8(rvalid ? v : uintx4{0, 0, 0, 0}); // padded rows may hold NaN
+    const int blk_stride = wgs_per_head * kNW;
+    int blk = wg_in_head * kNW + wave;
+    Row nxt{};
+    uintx4 qraw[8];
+    if (blk < nblocks) {
+        nxt = decode(blk);
+        load_q(nxt, qraw);
+    }
+
+    while (blk < nblocks) {
+        const int r0 = blk * kBlockRows;
+        const int next_blk = blk + blk_stride;
+        const Row cur = nxt;
+        const int rlen = cur.rlen < 0 ? 0 : (cur.rlen > a.S ? a.S : cur.rlen);
+        const bool rvalid = cur.rin && (int)cur.ri < rlen;
+        const bool any_valid = __builtin_amdgcn_ballot_w64(rvalid) != 0; // else: nothing but padding
+        unsigned short *orow =
+            og + (long long)cur.rb * a.o_sb + (long long)cur.ri * a.o_ss + (long long)cur.rh * a.o_sh;
+        // qraw holds this block's Q fragments until their last use, then the next block's.
+        // Padded rows are used as they are: a row's values only ever reach its own column of
+        // S^T and O^T, and padded rows are stored as zero.
+
+        // ---- suffix steps of this block: (candidate, 32-key tile) pairs, wave-uniform ----
+        const int last_row = r0 + kBlockRows - 1 < Mtot ? r0 + kBlockRows - 1 : Mtot - 1;
+        const int tok_first = fdiv(r0, a.div_g), tok_last = fdiv(last_row, a.div_g);
+        const int b_last = fdiv(tok_last, a.div_s);
+        int sb = fdiv(tok_first, a.div_s), sk0 = 0, skmax = -1; // current step: candidate, first key, last key
+        // advance (sb, sk0) to the next step that has a visible key; false when there is none
+        auto seek = [&]() {
+            while (sb <= b_last) {
+                const int len = len_of(sb);
+                const int i_lo = tok_first - sb * a.S > 0 ? tok_first - sb * a.S : 0;
+                const int i_hi = tok_last - sb * a.S < a.S - 1 ? tok_last - sb * a.S : a.S - 1;
+                skmax = i_hi < len - 1 ? i_hi : len - 1; // last suffix key any row of this block sees
+                if (i_lo < len && sk0 <= skmax)
+                    return true;
+                ++sb;
+                sk0 = 0;
             }
-        }
+            return false;
+        };
+        // Suffix K fragments straight from global memory in A-operand layout.  Rows past skmax
+        // are never visible: their address is clamped to row skmax instead of being zero-filled.
+        uintx4 skf[8], svf[2][4];
+        auto load_suffix_k = [&]() {
+            const int bc = sb < a.B ? sb : a.B - 1; // when there is no step the loads still happen, in bounds
+            int krow = sk0 + c32 < skmax ? sk0 + c32 : skmax;
+            krow = krow > 0 ? krow : 0;
+            const unsigned short *kp = ksg + (long long)bc * a.ks_sb + (long long)krow * a.ks_ss + 8 * h;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks)
+                skf[ks] = ld_global16(kp + 16 * ks);
+        };
+        // V rows of both 16-key steps in scratch-image order (clamped like K: a clamped row is
+        // finite data that only ever meets weight 0)
+        auto load_suffix_v = [&]() {
+            const int bc = sb < a.B ? sb : a.B - 1;
+            const unsigned short *vb = vsg + (long long)bc * a.ks_sb;
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const int frag = 2 * it + h; // fragment (dt = frag >> 1, u = frag & 1)
+                    int key = sk0 + 16 * j + 8 * (frag & 1) + sv_row_lo;
+                    key = key < skmax ? key : skmax;
+                    key = key > 0 ? key : 0;
+                    svf[j][it] = ld_global16(vb + (long long)key * a.ks_ss + (4 * (frag >> 1) + sv_chunk_lo) * 8);
+                }
+        };
+        bool have_suf = any_valid && seek();
+        load_suffix_k(); // needed last, requested first: loads retire in issue order
 
         RowState st;
         st.m = -INFINITY;
@@ -246,7 +323,7 @@ void resident_kernel(Args a, int wgs_per_head, int ntiles)
                 st.o[dt][e] = 0.f;
 
         // ---- prefix part: every row sees every prefix key ----
-        for (int kt = 0; kt < ntiles; ++kt) {
+        auto prefix_tile = [&](int kt) {
             floatx16 s;
 #pragma unroll
             for (int e = 0; e < 16; ++e)
@@ -254,13 +331,14 @@ void resident_kernel(Args a, int wgs_per_head, int ntiles)
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
                 const bf16x8 kf = as_bf16x8(*(lds_u128 *)(k_lane + kt * kTileBytes + ks * 1024));
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s, 0, 0, 0);
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, as_bf16x8(qraw[ks]), s, 0, 0, 0);
             }
             const int nvalid = a.P - kt * kTileKeys;
-            if (nvalid < kTileKeys) { // ragged last tile
+            if (nvalid < kTileKeys) { // ragged last tile: keys past the prefix are not visible
+                const int nv = nvalid - 4 * h; // element e holds key 8*(e/4) + e%4 + 4*h of the tile
 #pragma unroll
                 for (int e = 0; e < 16; ++e)
-                    if (8 * (e >> 2) + 4 * h + (e & 3) >= nvalid)
+                    if (8 * (e >> 2) + (e & 3) >= nv)
                         s[e] = -INFINITY;
             }
             bf16x8 pf[2];
@@ -271,106 +349,102 @@ void resident_kernel(Args a, int wgs_per_head, int ntiles)
                 for (int dt = 0; dt < 4; ++dt)
                     st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_fragment(v_lane + kt * kTileBytes, dt, j),
                                                                        pf[j], st.o[dt], 0, 0, 0);
-        }
+        };
+        const int nt = any_valid ? ntiles : 0;
+        for (int kt = 0; kt < nt - 1; ++kt)
+            prefix_tile(kt);
+        load_suffix_v(); // one tile ahead of its use
+        if (nt > 0)
+            prefix_tile(nt - 1);
 
         // ---- suffix part: causal attention to the own candidate's suffix K/V ----
-        {
-            const int last_row = r0 + kBlockRows - 1 < Mtot ? r0 + kBlockRows - 1 : Mtot - 1;
-            const int tok_first = fdiv(r0, a.div_g), tok_last = fdiv(last_row, a.div_g);
-            const int b_first = fdiv(tok_first, a.div_s), b_last = fdiv(tok_last, a.div_s);
-            for (int b = b_first; b <= b_last; ++b) { // wave-uniform
-                int len = a.len ? a.len[b] : a.S;
-                len = len < 0 ? 0 : (len > a.S ? a.S : len);
-                len = __builtin_amdgcn_readfirstlane(len);
-                const int i_lo = tok_first - b * a.S > 0 ? tok_first - b * a.S : 0;
-                const int i_hi = tok_last - b * a.S < a.S - 1 ? tok_last - b * a.S : a.S - 1;
-                const int kmax = i_hi < len - 1 ? i_hi : len - 1; // last suffix key any row here sees
-                if (i_lo >= len || kmax < 0)
-                    continue;
-                const unsigned short *kb = ksg + (long long)b * a.ks_sb;
-                const unsigned short *vb = vsg + (long long)b * a.ks_sb;
-                const int lim = (int)rb == b ? (int)ri : -1; // this row sees keys 0..lim of candidate b
-                for (int k0 = 0; k0 <= kmax; k0 += kTileKeys) {
-                    // K fragments straight from global memory; V rows of both 16-key steps
-                    uintx4 kf[8], vf[2][4];
-                    {
-                        const int key = k0 + c32;
-                        const bool ok = key <= kmax;
-                        const unsigned short *krow = kb + (long long)(ok ? key : 0) * a.ks_ss + 8 * h;
+        // One step (32 keys): scores, then - once the scores are out - `after_scores`, then
+        // mask, softmax and the value product through the scratch tile.
+        auto suffix_step = [&](auto after_scores) {
+            // this row sees keys 0..ri of its own candidate; element e holds key sk0 + 8*(e/4) + e%4 + 4*h
+            const int lim = ((int)cur.rb == sb ? (int)cur.ri : -1) - sk0 - 4 * h;
+            floatx16 s;
 #pragma unroll
-                        for (int ks = 0; ks < 8; ++ks) {
-                            uintx4 v = ld_global16(krow + 16 * ks);
-                            kf[ks] = ok ? v : uintx4{0, 0, 0, 0};
-                        }
-                    }
+            for (int e = 0; e < 16; ++e)
+                s[e] = 0.f;
 #pragma unroll
-                    for (int j = 0; j < 2; ++j)
+            for (int ks = 0; ks < 8; ++ks)
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(skf[ks]), as_bf16x8(qraw[ks]), s, 0, 0, 0);
+            after_scores();
 #pragma unroll
-                        for (int it = 0; it < 4; ++it) {
-                            const int frag = 2 * it + h; // fragment (dt = frag >> 1, u = frag & 1)
-                            const int key = k0 + 16 * j + 8 * (frag & 1) + sv_row_lo;
-                            const int chunk = 4 * (frag >> 1) + sv_chunk_lo;
-                            const bool ok = key <= kmax;
-                            uintx4 v = ld_global16(vb + (long long)(ok ? key : 0) * a.ks_ss + chunk * 8);
-                            vf[j][it] = ok ? v : uintx4{0, 0, 0, 0}; // V rows past the last visible key: zero, not NaN
-                        }
-                    floatx16 s;
+            for (int e = 0; e < 16; ++e)
+                s[e] = 8 * (e >> 2) + (e & 3) <= lim ? s[e] : -INFINITY;
+            bf16x8 pf[2];
+            softmax_tile(s, st, c, pf);
 #pragma unroll
-                    for (int e = 0; e < 16; ++e)
-                        s[e] = 0.f;
+            for (int j = 0; j < 2; ++j) {
 #pragma unroll
-                    for (int ks = 0; ks < 8; ++ks)
-                        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[ks]), qf[ks], s, 0, 0, 0);
+                for (int it = 0; it < 4; ++it)
+                    *(lds_u128 *)(scr + it * 1024 + lane * 16) = svf[j][it];
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                bf16x8 va[4];
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) {
-                        const int key = k0 + 8 * (e >> 2) + 4 * h + (e & 3);
-                        s[e] = key <= lim ? s[e] : -INFINITY;
-                    }
-                    bf16x8 pf[2];
-                    softmax_tile(s, st, c, pf);
+                for (int dt = 0; dt < 4; ++dt) {
+                    short4v lo = lds_read_tr(scr_lane + (dt * 2 + 0) * 512);
+                    short4v hi = lds_read_tr(scr_lane + (dt * 2 + 1) * 512);
+                    short8v v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    __builtin_memcpy(&va[dt], &v8, 16);
+                }
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-#pragma unroll
-                        for (int it = 0; it < 4; ++it)
-                            *(lds_u128 *)(scr + it * 1024 + lane * 16) = vf[j][it];
-                        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                        __builtin_amdgcn_wave_barrier();
-                        bf16x8 va[4];
-#pragma unroll
-                        for (int dt = 0; dt < 4; ++dt) {
-                            short4v lo = lds_read_tr(scr_lane + (dt * 2 + 0) * 512);
-                            short4v hi = lds_read_tr(scr_lane + (dt * 2 + 1) * 512);
-                            short8v v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                            __builtin_memcpy(&va[dt], &v8, 16);
-                        }
-                        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-                        for (int dt = 0; dt < 4; ++dt)
-                            st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[dt], pf[j], st.o[dt], 0, 0, 0);
-                    }
+                for (int dt = 0; dt < 4; ++dt)
+                    st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[dt], pf[j], st.o[dt], 0, 0, 0);
+            }
+        };
+        // The next block's row decode and Q go into the registers of this block's Q as soon as
+        // those have been used for the last time.
+        // (Requested unconditionally, for a clamped block index past the end: a load under a
+        // branch would have to be waited for and copied at the join.)
+        auto prefetch_next = [&]() {
+            blk = next_blk;
+            nxt = decode(blk < nblocks ? blk : nblocks - 1);
+            load_q(nxt, qraw);
+        };
+        if (ALIGNED1) {
+            // a block lies inside one candidate and the suffix fits one step: Q's last use is
+            // that step's score product, everything after it runs under the prefetch
+            if (have_suf)
+                suffix_step(prefetch_next);
+            else
+                prefetch_next();
+        } else {
+            while (have_suf) {
+                suffix_step([] {});
+                sk0 += kTileKeys;
+                have_suf = seek();
+                if (have_suf) { // further steps (long suffixes, several candidates per block)
+                    load_suffix_k();
+                    load_suffix_v();
                 }
             }
+            prefetch_next();
         }
 
         // ---- normalise and store (the division by the softmax denominator of Eq. 2) ----
         const float ltot = st.l + __shfl_xor(st.l, 32, 64);
-        if (rin) {
+        if (cur.rin) {
             const float inv = rvalid ? 1.0f / ltot : 0.f;
+            typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) {
-                    unsigned w0 = 0u, w1 = 0u;
-                    if (rvalid) {
-                        w0 = pack_bf16(st.o[dt][4 * kk + 0] * inv, st.o[dt][4 * kk + 1] * inv);
-                        w1 = pack_bf16(st.o[dt][4 * kk + 2] * inv, st.o[dt][4 * kk + 3] * inv);
+                    uintx2 w = {0u, 0u};
+                    if (rvalid) { // padded rows are stored as zero
+                        w[0] = pack_bf16(st.o[dt][4 * kk + 0] * inv, st.o[dt][4 * kk + 1] * inv);
+                        w[1] = pack_bf16(st.o[dt][4 * kk + 2] * inv, st.o[dt][4 * kk + 3] * inv);
                     }
-                    typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
-                    *reinterpret_cast<uintx2 *>(orow + 32 * dt + 8 * kk + 4 * h) = uintx2{w0, w1};
+                    *reinterpret_cast<uintx2 *>(orow + 32 * dt + 8 * kk + 4 * h) = w;
                 }
             if (a.lse && h == 0)
-                a.lse[((long long)rb * a.Hq + rh) * a.S + ri] =
+                a.lse[((long long)cur.rb * a.Hq + cur.rh) * a.S + cur.ri] =
                     rvalid ? (st.m + __builtin_log2f(ltot)) * kLn2 : -INFINITY;
         }
     }
@@ -391,10 +465,13 @@ hipError_t launch_resident(const Args &a, hipStream_t stream)
         hipError_t e = hipGetDevice(&dev);
         if (e == hipSuccess)
             e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+        const int max_lds = 2 * kMaxTiles * kTileBytes + kNW * kScrBytes;
         if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(resident_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    2 * kMaxTiles * kTileBytes + kNW * kScrBytes);
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(resident_kernel<false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(resident_kernel<true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
         if (e != hipSuccess)
             return e;
         num_cu = n > 0 ? n : 256;
@@ -410,7 +487,11 @@ hipError_t launch_resident(const Args &a, hipStream_t stream)
         per_head = useful;
     const unsigned grid = (unsigned)(per_head * a.Hkv);
     const size_t lds = (size_t)2 * ntiles * kTileBytes + kNW * kScrBytes;
-    hipLaunchKernelGGL(resident_kernel, dim3(grid), dim3(kNW * 64), lds, stream, a, (int)per_head, ntiles);
+    const bool aligned1 = ((long long)a.S * a.G) % kBlockRows == 0 && a.S <= kTileKeys;
+    if (aligned1)
+        hipLaunchKernelGGL(resident_kernel<true>, dim3(grid), dim3(kNW * 64), lds, stream, a, (int)per_head, ntiles);
+    else
+        hipLaunchKernelGGL(resident_kernel<false>, dim3(grid), dim3(kNW * 64), lds, stream, a, (int)per_head, ntiles);
     return hipGetLastError();
 }
 
