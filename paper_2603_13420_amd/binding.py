@@ -180,6 +180,28 @@ def pskv_attn_fwd(q, k_suf, v_suf, k_pre, v_pre, suf_len=None, out=None, lse=Non
     return out
 
 
+class PreparedCall:
+    """pskv_attn_fwd with every argument marshalled once: calling it costs one foreign call.
+    The tensors must stay alive and unmoved for as long as the object is used."""
+
+    def __init__(self, q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse=None, impl: str = "auto",
+                 scale: float = 0.0, stream: Optional[int] = None):
+        import torch
+        _check_inputs(q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse)
+        self._keep = (q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse)
+        self._p = _params_from_tensors(q, k_suf, k_pre, out, impl, scale)
+        if stream is None:
+            stream = torch.cuda.current_stream(q.device).cuda_stream
+        self._args = (ctypes.byref(self._p), _ptr(q), _ptr(k_suf), _ptr(v_suf), _ptr(k_pre), _ptr(v_pre),
+                      _ptr(suf_len), _ptr(out), _ptr(lse), None, 0, ctypes.c_void_p(stream))
+        self._fn = load().pskv_attn_fwd
+
+    def __call__(self):
+        rc = self._fn(*self._args)
+        if rc != PSKV_OK:
+            _raise(rc)
+
+
 def pskv_attn_fwd_timed(q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse=None, impl: str = "auto",
                         scale: float = 0.0, iters: int = 10, stream: Optional[int] = None) -> float:
     """Mean milliseconds of one call over `iters` back-to-back calls, measured with HIP events

@@ -339,28 +339,36 @@ __device__ inline void store_zero_block(const Args &a, const Ctx &X, const Row &
         a.lse[((long long)row.rb * a.Hq + row.rh) * a.S + row.ri] = -INFINITY;
 }
 
-// Copies the prefix K/V of one head into the fragment-major LDS images (whole workgroup).
-// Slot i of a tile image is bytes [i*16, i*16+16); which (key, chunk) goes there follows from
-// the layouts described at the top of the file.  Rows past the prefix are zero.
-__device__ inline void stage_prefix(const Args &a, int head, int ntiles, lds_u8 *kimg, lds_u8 *vimg, int tid,
-                                    int nthreads)
+// Copies the prefix K/V of one head into the fragment-major LDS images (whole workgroup of 512
+// threads).  Slot i of a tile image is bytes [i*16, i*16+16); which (key, chunk) goes there
+// follows from the layouts described at the top of the file.  Rows past the prefix are zero.
+// All global loads are issued before the first LDS write, so their latencies overlap.
+__device__ inline void stage_prefix(const Args &a, int head, int ntiles, lds_u8 *kimg, lds_u8 *vimg, int tid)
 {
     const unsigned short *kpg = reinterpret_cast<const unsigned short *>(a.kp) + (long long)head * a.kp_sh;
     const unsigned short *vpg = reinterpret_cast<const unsigned short *>(a.vp) + (long long)head * a.kp_sh;
-    for (int i = tid; i < ntiles * 512; i += nthreads) {
-        const int kt = i >> 9, slot = i & 511;
-        const int k_row = slot & 31, k_chunk = slot >> 5; // K: key-in-tile, 16-byte chunk of the row
-        const int p5 = slot & 31, fr = slot >> 5;         // V: piece within a 512-byte fragment, fragment id
-        const int v_row = 16 * ((fr >> 1) & 1) + 8 * (fr & 1) + 4 * ((p5 >> 4) & 1) + ((p5 >> 1) & 3);
-        const int v_chunk = 4 * (fr >> 2) + 2 * ((p5 >> 3) & 1) + (p5 & 1);
+    const int k_row = tid & 31, k_chunk = tid >> 5; // K: key-in-tile, 16-byte chunk of the row
+    const int p5 = tid & 31, fr = tid >> 5;         // V: piece within a 512-byte fragment, fragment id
+    const int v_row = 16 * ((fr >> 1) & 1) + 8 * (fr & 1) + 4 * ((p5 >> 4) & 1) + ((p5 >> 1) & 3);
+    const int v_chunk = 4 * (fr >> 2) + 2 * ((p5 >> 3) & 1) + (p5 & 1);
+    uintx4 kv[kMaxTiles], vv[kMaxTiles];
+#pragma unroll
+    for (int kt = 0; kt < kMaxTiles; ++kt) {
+        // clamped, in-bounds addresses for every slot; what lies past the prefix is zeroed below
         const int kkey = kt * kTileKeys + k_row, vkey = kt * kTileKeys + v_row;
-        uintx4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
-        if (kkey < a.P)
-            kv = ld_global16(kpg + (long long)kkey * a.kp_sp + k_chunk * 8);
-        if (vkey < a.P)
-            vv = ld_global16(vpg + (long long)vkey * a.kp_sp + v_chunk * 8);
-        *(lds_u128 *)(kimg + i * 16) = kv;
-        *(lds_u128 *)(vimg + i * 16) = vv;
+        const int kc = kkey < a.P ? kkey : (a.P > 0 ? a.P - 1 : 0), vc = vkey < a.P ? vkey : (a.P > 0 ? a.P - 1 : 0);
+        if (kt < ntiles) {
+            kv[kt] = ld_global16(kpg + (long long)kc * a.kp_sp + k_chunk * 8);
+            vv[kt] = ld_global16(vpg + (long long)vc * a.kp_sp + v_chunk * 8);
+        }
+    }
+#pragma unroll
+    for (int kt = 0; kt < kMaxTiles; ++kt) {
+        if (kt < ntiles) {
+            const int kkey = kt * kTileKeys + k_row, vkey = kt * kTileKeys + v_row;
+            *(lds_u128 *)(kimg + kt * kTileBytes + tid * 16) = kkey < a.P ? kv[kt] : uintx4{0, 0, 0, 0};
+            *(lds_u128 *)(vimg + kt * kTileBytes + tid * 16) = vkey < a.P ? vv[kt] : uintx4{0, 0, 0, 0};
+        }
     }
 }
 
@@ -481,7 +489,7 @@ void resident_general_kernel(Args a, int wgs_per_head, int ntiles)
     const int tid = threadIdx.x;
     const int head = blockIdx.x % a.Hkv; // consecutive workgroup ids (one per XCD in turn) take consecutive heads
     const Ctx X = make_ctx(a, smem, ntiles, tid, head);
-    stage_prefix(a, head, ntiles, smem, smem + ntiles * kTileBytes, tid, kNW * 64);
+    stage_prefix(a, head, ntiles, smem, smem + ntiles * kTileBytes, tid);
     __syncthreads();
     const int nblocks = (X.Mtot + kBlockRows - 1) / kBlockRows;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -600,7 +608,7 @@ void resident_pipelined_kernel(Args a, int wgs_per_head, int ntiles)
     uintx4 q[8]; // this block's Q fragments until their last use, then the next block's
     load_q(a, X, nxt, q);
 
-    stage_prefix(a, head, ntiles, smem, smem + ntiles * kTileBytes, tid, kNW * 64);
+    stage_prefix(a, head, ntiles, smem, smem + ntiles * kTileBytes, tid);
     __syncthreads();
 
     while (blk < nblocks) {
@@ -636,11 +644,7 @@ void resident_pipelined_kernel(Args a, int wgs_per_head, int ntiles)
 
         // ---- pipeline over the prefix tiles: scores of tile kt+1 under the weights of tile kt ----
         pipe_step<true, false>(X.k_lane + kTileBytes, skf, X.v_lane, q, s, X.c, m, l, o);
-#ifdef EXP_FEWTILES
-        for (int kt = 1; kt < 2; ++kt)
-#else
         for (int kt = 1; kt < ntiles - 1; ++kt)
-#endif
             pipe_step<false, false>(X.k_lane + (kt + 1) * kTileBytes, skf, X.v_lane + kt * kTileBytes, q, s, X.c, m, l, o);
         if (a.P & (kTileKeys - 1)) { // ragged last prefix tile: keys past the prefix are not visible
             const int nv = a.P - (ntiles - 1) * kTileKeys - 4 * X.h;
@@ -681,9 +685,6 @@ void resident_pipelined_kernel(Args a, int wgs_per_head, int ntiles)
         }
 
         any_bad |= __builtin_amdgcn_ballot_w64(rvalid && !(l < kBig)) != 0;
-#ifdef EXP_NOSTORE
-        if (l == 12345.678f)
-#endif
         store_block(a, X, r0, row, rvalid, m, l, o);
     }
 

@@ -138,6 +138,31 @@ def test_runs_on_a_side_stream_and_is_deterministic(pk):
     pu.compare(pu.out_to_f64(outs[0]), ref, inp.suf_len, "bf16", "side stream")
 
 
+BF16_ONE, BF16_EIGHT = 0x3F80, 0x4100
+
+
+@pytest.mark.parametrize("impl", ["simple", "mfma"])
+@pytest.mark.parametrize("B,P,S,lo,hi,Hq,Hkv", [
+    (4, 256, 24, 16, 24, 8, 2),     # blocks inside one candidate, one suffix step: pipelined kernel
+    (5, 100, 20, 20, 20, 4, 4),     # several candidates per block: general resident kernel
+    (3, 700, 40, 33, 40, 2, 2),     # long prefix: streaming kernel
+])
+def test_scores_far_above_the_first_tile(pk, impl, B, P, S, lo, hi, Hq, Hkv):
+    """A late prefix key and a late suffix key whose scores exceed everything seen before by
+    ~90 in natural units: any softmax that fixes its reference early must notice and recover
+    (the plain definition, which the oracle follows, subtracts the true maximum)."""
+    w = gen.custom_workload(f"spike_{B}_{P}_{S}", B, P, S, lo, hi, Hq, Hkv, 128, "bf16", index=600 + P)
+    inp = gen.make_inputs(w, pad="nan")
+    # candidate 1: all-ones queries against an all-eights prefix key near the end of the prefix
+    inp.q[1, :inp.suf_len[1]] = BF16_ONE
+    inp.k_pre[P - 3] = BF16_EIGHT
+    # candidate 2: all-ones queries against an all-eights key at its own last suffix position
+    inp.q[2, :inp.suf_len[2]] = BF16_ONE
+    inp.k_suf[2, inp.suf_len[2] - 1] = BF16_EIGHT
+    res = run_case(pk, inp, impl, what=f"spike {w.name}")
+    assert res["n"] > 0
+
+
 def test_mha7b_full_size_full_compare(pk):
     """7B-class MHA shape at its full size, every output element compared."""
     inp = gen.make_inputs(gen.WORKLOADS["mha7b_bf16"], pad="nan")
