@@ -39,6 +39,14 @@ def alg_counts(w, suf_len):
     return flops, bytes_, prefix_bytes, exps
 
 
+# HBM traffic of one launch as read by rocprofv3 (FETCH_SIZE / WRITE_SIZE, KiB per dispatch), with
+# the factor by which the same counter under- or over-reads a plain copy kernel of known size.
+# Offline measurements: the commands and raw readings are in profiles/*_hbm_traffic.txt.
+HBM_TRAFFIC = {
+    "gqa8b_bf16": {"fetch_kib": 149671.0, "fetch_scale": 2.0, "write_kib": 196619.0, "write_scale": 1.0},
+}
+
+
 def cpu_baseline(inp, budget_s=12.0):
     """Time the CPU oracle, as it stands, on a bounded sample of the same workload."""
     import numpy as np
@@ -46,19 +54,21 @@ def cpu_baseline(inp, budget_s=12.0):
     w = inp.w
     n = min(w.B, 8)
     t_total, done = 0.0, 0
-    # grow the sample until roughly budget_s seconds of oracle time have been spent
-    while True:
-        sub = inp.take(np.arange(done, done + n))
+    # grow the sample until roughly budget_s seconds of oracle time have been spent,
+    # wrapping round the batch when the whole workload takes less than that
+    while t_total < budget_s:
+        first = done % w.B
+        n = min(n, w.B - first)
+        sub = inp.take(np.arange(first, first + n))
         t0 = time.perf_counter()
         orc.attn(sub.q, sub.k_suf, sub.v_suf, sub.k_pre, sub.v_pre, sub.suf_len, sub.scale, w.dtype)
         t_total += time.perf_counter() - t0
         done += n
-        if t_total >= budget_s or done >= w.B:
-            break
         rate = done / t_total
-        n = int(max(1, min(w.B - done, rate * (budget_s - t_total))))
+        n = int(max(1, min(w.B, rate * max(budget_s - t_total, 0.0) / 2 + 1)))
     return {"value": done / t_total, "unit": "candidates/s", "cores": orc.threads(), "kind": "oracle",
-            "sample": f"first {done} of {w.B} candidates of {w.name} (all heads), {t_total:.1f} s of oracle time"}
+            "sample": f"{done} candidates (the {w.B} of {w.name} taken in order, wrapping round; all heads), "
+                      f"{t_total:.1f} s of oracle time"}
 
 
 def main():
@@ -70,6 +80,9 @@ def main():
     ap.add_argument("--impl", default="auto")
     ap.add_argument("--sets", type=int, default=0, help="rotating input/output buffer sets (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain element-wise copy of known size (the reference that the "
+                         "FETCH_SIZE / WRITE_SIZE counter readings are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path needs no exchange between "
@@ -84,6 +97,17 @@ def main():
 
     pk.load()
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    if args.copy_calibration:
+        # 1 GiB read + 1 GiB written per launch by one element-wise kernel
+        n = 1 << 29
+        src = torch.zeros(n, dtype=torch.bfloat16, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "launches": 10, "read_bytes_per_launch": 2 * n,
+                          "written_bytes_per_launch": 2 * n}), flush=True)
+        return
     w = gen.WORKLOADS[args.workload]
     inp = gen.make_inputs(w, pad="zero", workers=16)
     flops, bytes_, prefix_bytes, exps = alg_counts(w, inp.suf_len)
@@ -128,13 +152,16 @@ def main():
     ev_ms = ev0.elapsed_time(ev1) / args.steps
     ms_per_step = wall * 1e3 / args.steps
 
-    # Per-launch kernel duration measured by the library itself with HIP events on the same
-    # stream (back-to-back launches, one buffer set per measurement, averaged over the sets).
+    # Per-launch kernel duration: HIP events over the timed region on the launch stream.  The
+    # launches are queued back to back, so the event span divided by the launch count is the
+    # average duration of one launch (plus the idle gap between two launches, if any).
+    kern_ms = ev_ms
+    # For comparison, launches timed one at a time by the library's own event-bracketed helper.
     per_set = [pk.pskv_attn_fwd_timed(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"],
                                       d["suf_len"], d["out"], impl=args.impl, scale=inp.scale, iters=1,
                                       stream=stream)
-               for _ in range(max(1, min(50, args.steps // nsets))) for d in sets]
-    kern_ms = float(np.mean(per_set))
+               for _ in range(max(1, min(20, args.steps // nsets))) for d in sets]
+    isolated_ms = float(np.mean(per_set))
 
     # quick self-check of the timed configuration on a few candidates (not timed)
     cand = np.array([0, w.B // 2, w.B - 1])
@@ -153,8 +180,11 @@ def main():
     else:
         roof = {"bound": "alu", "achieved": flops / (kern_ms * 1e-3) / 1e12, "peak": 157.3, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    tr = HBM_TRAFFIC.get(w.name) if args.impl == "auto" else None
+    roof["traffic"] = (tr["fetch_kib"] * tr["fetch_scale"] + tr["write_kib"] * tr["write_scale"]) * 1024 if tr else None
+    roof["traffic_unit"] = "bytes per launch"
     roof["kernel_ms"] = kern_ms
+    roof["kernel_ms_isolated_launches"] = isolated_ms
     roof["alg_flops_per_launch"] = flops
     hbm = {"bound": "hbm", "achieved": bytes_ / (kern_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
            "alg_bytes_per_launch": bytes_, "prefix_bytes_once": prefix_bytes}
