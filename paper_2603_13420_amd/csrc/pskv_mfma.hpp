@@ -1,0 +1,525 @@
+// Device code shared by the matrix-core kernels of batched candidate-suffix attention for
+// gfx950 (bf16 tensors, head dim 128): operand layouts, the per-row softmax state, suffix
+// loads, the output store and the software-pipelined tile step.
+//
+// Matrix-core formulation (v_mfma_f32_32x32x16_bf16, fp32 accumulate), transposed so that a
+// lane owns one query column q = lane % 32:
+//     S^T[key][q] = sum_d K[key][d] Q[q][d]           A = K fragment,  B = Q fragment
+//     O^T[d][q]  += sum_key V[key][d] P^T[key][q]     A = V^T fragment, B = P^T fragment
+// The accumulator of the first product holds, for lane half h = lane/32, keys 8*kk + 4*h + t
+// of the tile in element 4*kk + t.  Elements 8j..8j+7 are used unchanged as the B fragment of
+// contraction step j of the second product, which fixes the order in which V rows enter its
+// A fragment: slot (h, e) of step j is key 16*j + 8*(e/4) + 4*h + e%4.
+//
+// LDS images of a 32-key tile are stored "fragment-major": the 16 bytes (K) or 8 bytes (V)
+// that lane l reads for a given fragment sit at fragment_base + l*16 (or l*8), so every
+// fragment read is one contiguous, conflict-free wave access with an immediate offset and no
+// address arithmetic.
+//   K image: fragment ks (16 d) at ks*1024; lane (key = l%32, h) holds d = 16*ks + 8*h ..+7
+//   V image: fragment (dt, j, u) at ((dt*2 + j)*2 + u)*512; lane l = 32*h + 16*w + t names
+//            key 16*j + 8*u + 4*h + t/4, d = 32*dt + 16*w + 4*(t%4) ..+3; the transposing
+//            read then hands lane l the 4 keys 16*j + 8*u + 4*h + 0..3 at d = 32*dt + l%32.
+// With both images a 16-byte chunk (key, c) of the row-major global tile lands at
+// image_base + tid*16 when thread tid of a 512-thread group fetches the right (key, c):
+// see TileSlot below.
+#pragma once
+#include "pskv_internal.h"
+
+namespace pskv {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef short short8v __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kD = 128;
+constexpr int kBlockRows = 32;          // query rows per wavefront block
+constexpr int kNW = 8;                  // wavefronts per workgroup
+constexpr int kTileKeys = 32;           // keys per LDS tile
+constexpr int kTileBytes = kTileKeys * kD * 2; // 8 KB
+constexpr int kScrBytes = 4096;         // per-wave V scratch: 16 keys
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kBig = 1.0e18f;         // row sums at or above this trigger a rescale
+
+typedef __attribute__((address_space(3))) unsigned char lds_u8;
+typedef __attribute__((address_space(3))) uintx4 lds_u128;
+
+__device__ inline unsigned fdiv(unsigned n, FastDiv d) { return (unsigned)(((unsigned long long)n * d.mul) >> d.shift); }
+
+__device__ inline uintx4 ld_global16(const unsigned short *p) { return *reinterpret_cast<const uintx4 *>(p); }
+
+__device__ inline bf16x8 as_bf16x8(uintx4 v)
+{
+    bf16x8 r;
+    __builtin_memcpy(&r, &v, 16);
+    return r;
+}
+
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ inline unsigned pack_bf16(float lo, float hi)
+{
+    floatx2 f = {lo, hi};
+    bf16x2 h = __builtin_convertvector(f, bf16x2);
+    unsigned r;
+    __builtin_memcpy(&r, &h, 4);
+    return r;
+}
+
+__device__ inline short4v lds_read_tr(lds_u8 *p)
+{
+    typedef short4v __attribute__((address_space(3))) * tr_ptr;
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((tr_ptr)p);
+}
+
+// A fragment of V^T for contraction step j of tile image `vt`, output-column tile dt.
+__device__ inline bf16x8 v_fragment(lds_u8 *vt_lane, int dt, int j)
+{
+    short4v lo = lds_read_tr(vt_lane + ((dt * 2 + j) * 2 + 0) * 512);
+    short4v hi = lds_read_tr(vt_lane + ((dt * 2 + j) * 2 + 1) * 512);
+    short8v v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    bf16x8 vf;
+    __builtin_memcpy(&vf, &v8, 16);
+    return vf;
+}
+
+struct RowState {
+    float m;       // reference maximum of the scaled scores, log2 units (-inf: nothing seen yet)
+    float l;       // this lane's share of the running sum (the other half-wave holds the rest)
+    floatx16 o[4]; // O^T accumulators: o[dt][4*kk + t] = O^T[32*dt + 8*kk + 4*h + t][q]
+};
+
+// Softmax step for one 32-key tile whose raw (masked: -inf) scores are in s.
+// Fast path: weights are taken relative to the row's current reference maximum without looking
+// at this tile's maximum; exp2 of a larger score simply gives a weight above one, which fp32
+// sums and bf16 weights hold at full relative precision.  Only when some row's tile sum is not
+// below kBig (first tile of a row, or scores far above the reference) does the wavefront take
+// the classic online-softmax step: new maximum, rescale of sum and output, weights recomputed.
+__device__ inline void softmax_tile(const floatx16 &s, RowState &st, float c, bf16x8 (&pf)[2])
+{
+    float p[16];
+    float rs = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        p[e] = fast_exp2(__builtin_fmaf(s[e], c, -st.m));
+        rs += p[e];
+    }
+    if (__builtin_amdgcn_ballot_w64(!(rs < kBig)) != 0) {
+        float tmax = s[0];
+#pragma unroll
+        for (int e = 1; e < 16; ++e)
+            tmax = fmaxf(tmax, s[e]);
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+        const float mnew = fmaxf(st.m, tmax * c);
+        const float msafe = mnew == -INFINITY ? 0.f : mnew; // nothing visible yet: weights all 0
+        const float alpha = fast_exp2(st.m - msafe);
+        st.l *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+            st.o[dt] *= alpha;
+        st.m = mnew;
+        rs = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            p[e] = fast_exp2(__builtin_fmaf(s[e], c, -msafe));
+            rs += p[e];
+        }
+    }
+    st.l += rs;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        uintx4 w = {pack_bf16(p[8 * j + 0], p[8 * j + 1]), pack_bf16(p[8 * j + 2], p[8 * j + 3]),
+                    pack_bf16(p[8 * j + 4], p[8 * j + 5]), pack_bf16(p[8 * j + 6], p[8 * j + 7])};
+        pf[j] = as_bf16x8(w);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Shared per-lane context
+// ------------------------------------------------------------------------------------------
+struct Ctx {
+    int lane, h, c32, head, Mtot;
+    float c;          // softmax scale in log2 units
+    lds_u8 *k_lane;   // K images + lane*16
+    lds_u8 *v_lane;   // V images + lane*8
+    lds_u8 *scr;      // this wavefront's V scratch
+    int sv_row_lo;    // suffix V staging: key of this lane within a 16-key step (+ 8*(fragment & 1))
+    int sv_chunk_lo;  // ... and its 16-byte chunk (+ 4*(fragment >> 1))
+    const unsigned short *ksg, *vsg; // suffix K/V of this KV head
+};
+
+// Row bookkeeping of one lane for one 32-row block.
+struct Row {
+    unsigned rb, ri; // candidate and suffix position of the lane's row
+    int rh;          // query head
+    int rlen;        // suffix length of that candidate as stored (not yet clamped)
+    bool rin;        // the row exists (r < B*S*G)
+};
+
+__device__ inline int clamp_len(const Args &a, int len) { return len < 0 ? 0 : (len > a.S ? a.S : len); }
+
+// Wave-uniform clamped suffix length of candidate b.  Read through the constant address space
+// (suf_len is never written during the call), which makes it a scalar load that does not queue
+// behind the vector loads in flight.
+__device__ inline int len_uniform(const Args &a, int b)
+{
+    typedef const __attribute__((address_space(4))) int *const_int_ptr;
+    if (!a.len)
+        return a.S;
+    return clamp_len(a, ((const_int_ptr)(unsigned long long)a.len)[__builtin_amdgcn_readfirstlane(b)]);
+}
+
+__device__ inline Row decode_row(const Args &a, const Ctx &X, int blk, int head)
+{
+    Row x;
+    const int r = blk * kBlockRows + X.c32;
+    x.rin = r < X.Mtot;
+    const unsigned rr = x.rin ? r : X.Mtot - 1;
+    const unsigned tok = fdiv(rr, a.div_g), gq = rr - tok * a.G;
+    x.rb = fdiv(tok, a.div_s);
+    x.ri = tok - x.rb * a.S;
+    x.rh = head * a.G + gq;
+    x.rlen = a.len ? a.len[x.rb] : a.S;
+    return x;
+}
+
+__device__ inline Row decode_row(const Args &a, const Ctx &X, int blk) { return decode_row(a, X, blk, X.head); }
+
+// Q fragments of a block: lane (row c32, half h) holds d = 16*ks + 8*h ..+7 for ks = 0..7.
+// Padded rows are loaded as they are: a row's values only ever reach its own column of S^T
+// and O^T, and padded rows are stored as zero.
+__device__ inline void load_q(const Args &a, const Ctx &X, const Row &x, uintx4 (&dst)[8])
+{
+    const unsigned short *qrow = reinterpret_cast<const unsigned short *>(a.q) + (long long)x.rb * a.q_sb +
+                                 (long long)x.ri * a.q_ss + (long long)x.rh * a.q_sh + 8 * X.h;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+        dst[ks] = ld_global16(qrow + 16 * ks);
+}
+
+// Suffix K fragments of step (candidate b, keys k0..k0+31) straight from global memory in
+// A-operand layout.  Rows past kmax are never visible: their address is clamped to row kmax
+// (and to row 0, candidate B-1, so that the loads stay in bounds even when there is no step).
+__device__ inline void load_suffix_k(const Args &a, const Ctx &X, int b, int k0, int kmax, uintx4 (&kf)[8])
+{
+    const int bc = b < a.B ? b : a.B - 1;
+    int krow = k0 + X.c32 < kmax ? k0 + X.c32 : kmax;
+    krow = krow > 0 ? krow : 0;
+    const unsigned short *kp = X.ksg + (long long)bc * a.ks_sb + (long long)krow * a.ks_ss + 8 * X.h;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+        kf[ks] = ld_global16(kp + 16 * ks);
+}
+
+// Suffix V rows of both 16-key steps in scratch-image order (clamped like K: a clamped row is
+// finite data that only ever meets weight 0).
+__device__ inline void load_suffix_v(const Args &a, const Ctx &X, int b, int k0, int kmax, uintx4 (&vf)[2][4])
+{
+    const int bc = b < a.B ? b : a.B - 1;
+    const unsigned short *vb = X.vsg + (long long)bc * a.ks_sb;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int frag = 2 * it + X.h; // fragment (dt = frag >> 1, u = frag & 1)
+            int key = k0 + 16 * j + 8 * (frag & 1) + X.sv_row_lo;
+            key = key < kmax ? key : kmax;
+            key = key > 0 ? key : 0;
+            vf[j][it] = ld_global16(vb + (long long)key * a.ks_ss + (4 * (frag >> 1) + X.sv_chunk_lo) * 8);
+        }
+}
+
+// O^T += V^T P^T for one 16-key step whose V rows are in registers: through the scratch tile.
+__device__ inline void pv_from_scratch(const Ctx &X, const uintx4 (&vstep)[4], bf16x8 pfj, floatx16 (&o)[4])
+{
+#pragma unroll
+    for (int it = 0; it < 4; ++it)
+        *(lds_u128 *)(X.scr + it * 1024 + X.lane * 16) = vstep[it];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    bf16x8 va[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+        short4v lo = lds_read_tr(X.scr + X.lane * 8 + (dt * 2 + 0) * 512);
+        short4v hi = lds_read_tr(X.scr + X.lane * 8 + (dt * 2 + 1) * 512);
+        short8v v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        __builtin_memcpy(&va[dt], &v8, 16);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[dt], pfj, o[dt], 0, 0, 0);
+}
+
+// Normalise and store one block (the division by the softmax denominator of Eq. 2); padded
+// rows are stored as zero.  In the accumulators a lane holds scattered 4-element pieces of its
+// row; stored like that, every memory request would carry 16 bytes.  So the block goes through
+// the wavefront's scratch tile in two passes (output columns 0..63, then 64..127), written by
+// the owners of the rows and read back so that 8 consecutive lanes store 128 contiguous bytes
+// of one row.  Scratch layout: row*128 + ((chunk ^ row%8) * 16), chunk = 16 bytes.
+__device__ inline void store_block(const Args &a, const Ctx &X, int r0, const Row &row, bool rvalid, float m, float l,
+                                   const floatx16 (&o)[4])
+{
+    typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+    typedef __attribute__((address_space(3))) uintx2 lds_u64;
+    const float ltot = l + __shfl_xor(l, 32, 64);
+    const float inv = 1.0f / ltot;
+    // rows this lane stores: 8*u + lane/8 for u = 0..3, 16 bytes at chunk lane%8 of each pass
+    unsigned short *dst[4];
+    bool dst_ok[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int r = r0 + 8 * u + (X.lane >> 3);
+        dst_ok[u] = r < X.Mtot;
+        const unsigned rr = dst_ok[u] ? r : X.Mtot - 1;
+        const unsigned tok = fdiv(rr, a.div_g), gq = rr - tok * a.G;
+        const unsigned b = fdiv(tok, a.div_s), i = tok - b * a.S;
+        dst[u] = reinterpret_cast<unsigned short *>(a.out) + (long long)b * a.o_sb + (long long)i * a.o_ss +
+                 (long long)(X.head * a.G + gq) * a.o_sh + 8 * (X.lane & 7);
+    }
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+        for (int dl = 0; dl < 2; ++dl)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const int dt = 2 * pass + dl;
+                uintx2 w = {0u, 0u};
+                if (rvalid) { // a padded row may carry NaN; it is stored as zero
+                    w[0] = pack_bf16(o[dt][4 * kk + 0] * inv, o[dt][4 * kk + 1] * inv);
+                    w[1] = pack_bf16(o[dt][4 * kk + 2] * inv, o[dt][4 * kk + 3] * inv);
+                }
+                *(lds_u64 *)(X.scr + X.c32 * 128 + (((4 * dl + kk) ^ (X.c32 & 7)) << 4) + 8 * X.h) = w;
+            }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int rl = 8 * u + (X.lane >> 3);
+            const uintx4 v = *(lds_u128 *)(X.scr + rl * 128 + (((X.lane & 7) ^ (rl & 7)) << 4));
+            if (dst_ok[u])
+                *reinterpret_cast<uintx4 *>(dst[u] + 64 * pass) = v;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+    if (row.rin && a.lse && X.h == 0)
+        a.lse[((long long)row.rb * a.Hq + row.rh) * a.S + row.ri] =
+            rvalid ? (m + __builtin_log2f(ltot)) * kLn2 : -INFINITY;
+}
+
+// Zeros for a block that holds nothing but padding.
+__device__ inline void store_zero_block(const Args &a, const Ctx &X, const Row &row)
+{
+    if (!row.rin)
+        return;
+    unsigned short *orow = reinterpret_cast<unsigned short *>(a.out) + (long long)row.rb * a.o_sb +
+                           (long long)row.ri * a.o_ss + (long long)row.rh * a.o_sh;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+        *reinterpret_cast<uintx4 *>(orow + 64 * X.h + 8 * u) = uintx4{0, 0, 0, 0};
+    if (a.lse && X.h == 0)
+        a.lse[((long long)row.rb * a.Hq + row.rh) * a.S + row.ri] = -INFINITY;
+}
+
+// Which 16-byte chunk of a row-major 32-key tile thread tid of a 512-thread group fetches so
+// that, written at image_base + tid*16, the chunks form the fragment-major K and V images.
+struct TileSlot {
+    int k_row, k_chunk, v_row, v_chunk;
+};
+
+__device__ inline TileSlot make_tile_slot(int tid)
+{
+    TileSlot t;
+    t.k_row = tid & 31;  // K: key within the tile ...
+    t.k_chunk = tid >> 5; // ... and 16-byte chunk of its row
+    const int p5 = tid & 31, fr = tid >> 5; // V: piece within a 512-byte fragment, fragment id
+    t.v_row = 16 * ((fr >> 1) & 1) + 8 * (fr & 1) + 4 * ((p5 >> 4) & 1) + ((p5 >> 1) & 3);
+    t.v_chunk = 4 * (fr >> 2) + 2 * ((p5 >> 3) & 1) + (p5 & 1);
+    return t;
+}
+
+// This thread's K and V chunks of prefix tile kt (rows clamped into the prefix: what lies past
+// it is zeroed when the chunks are written, see write_tile_chunks).
+__device__ inline void load_tile_chunks(const Args &a, const unsigned short *kpg, const unsigned short *vpg,
+                                        const TileSlot &t, int kt, uintx4 &kv, uintx4 &vv)
+{
+    const int last = a.P > 0 ? a.P - 1 : 0;
+    const int kkey = kt * kTileKeys + t.k_row, vkey = kt * kTileKeys + t.v_row;
+    kv = ld_global16(kpg + (long long)(kkey < a.P ? kkey : last) * a.kp_sp + t.k_chunk * 8);
+    vv = ld_global16(vpg + (long long)(vkey < a.P ? vkey : last) * a.kp_sp + t.v_chunk * 8);
+}
+
+__device__ inline void write_tile_chunks(const Args &a, const TileSlot &t, int kt, lds_u8 *kimg, lds_u8 *vimg, int tid,
+                                         const uintx4 &kv, const uintx4 &vv)
+{
+    const int kkey = kt * kTileKeys + t.k_row, vkey = kt * kTileKeys + t.v_row;
+    *(lds_u128 *)(kimg + tid * 16) = kkey < a.P ? kv : uintx4{0, 0, 0, 0};
+    *(lds_u128 *)(vimg + tid * 16) = vkey < a.P ? vv : uintx4{0, 0, 0, 0};
+}
+
+// Classic online-softmax step over one prefix tile whose images are in LDS (k_lane and v_lane
+// already include the lane offsets lane*16 and lane*8); nvalid = prefix keys in this tile.
+__device__ inline void prefix_tile_classic(const Ctx &X, lds_u8 *k_lane, lds_u8 *v_lane, int nvalid,
+                                           const uintx4 (&q)[8], RowState &st)
+{
+    floatx16 s;
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+        s[e] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 kf = as_bf16x8(*(lds_u128 *)(k_lane + ks * 1024));
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, as_bf16x8(q[ks]), s, 0, 0, 0);
+    }
+    if (nvalid < kTileKeys) { // ragged last tile: keys past the prefix are not visible
+        const int nv = nvalid - 4 * X.h; // element e holds key 8*(e/4) + e%4 + 4*h of the tile
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            if (8 * (e >> 2) + (e & 3) >= nv)
+                s[e] = -INFINITY;
+    }
+    bf16x8 pf[2];
+    softmax_tile(s, st, X.c, pf);
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+            st.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_fragment(v_lane, dt, j), pf[j], st.o[dt], 0, 0, 0);
+}
+
+// Causal suffix part of one 32-row block in full generality: the block may span several
+// candidates and a candidate's suffix several 32-key steps; (candidate, step) pairs are
+// wave-uniform.
+__device__ inline void suffix_classic(const Args &a, const Ctx &X, int r0, const Row &row, const uintx4 (&q)[8],
+                                      RowState &st)
+{
+    const int last_row = r0 + kBlockRows - 1 < X.Mtot ? r0 + kBlockRows - 1 : X.Mtot - 1;
+    const int tok_first = fdiv(r0, a.div_g), tok_last = fdiv(last_row, a.div_g);
+    const int b_last = fdiv(tok_last, a.div_s);
+    for (int b = fdiv(tok_first, a.div_s); b <= b_last; ++b) {
+        const int len = len_uniform(a, b);
+        const int i_lo = tok_first - b * a.S > 0 ? tok_first - b * a.S : 0;
+        const int i_hi = tok_last - b * a.S < a.S - 1 ? tok_last - b * a.S : a.S - 1;
+        const int kmax = i_hi < len - 1 ? i_hi : len - 1; // last suffix key any row of this block sees
+        if (i_lo >= len)
+            continue;
+        for (int k0 = 0; k0 <= kmax; k0 += kTileKeys) {
+            uintx4 kf[8], vf[2][4];
+            load_suffix_k(a, X, b, k0, kmax, kf);
+            load_suffix_v(a, X, b, k0, kmax, vf);
+            // the row sees keys 0..ri of its own candidate; element e holds key k0 + 8*(e/4) + e%4 + 4*h
+            const int lim = ((int)row.rb == b ? (int)row.ri : -1) - k0 - 4 * X.h;
+            floatx16 s;
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                s[e] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks)
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[ks]), as_bf16x8(q[ks]), s, 0, 0, 0);
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                s[e] = 8 * (e >> 2) + (e & 3) <= lim ? s[e] : -INFINITY;
+            bf16x8 pf[2];
+            softmax_tile(s, st, X.c, pf);
+            pv_from_scratch(X, vf[0], pf[0], st.o);
+            pv_from_scratch(X, vf[1], pf[1], st.o);
+        }
+    }
+}
+
+// Suffix step with a fixed reference maximum m (pipelined kernels): raw scores s of the keys
+// k0..k0+31 of the row's own candidate, causal mask, weights, value product through the
+// scratch tile.
+__device__ inline void suffix_step_fixed(const Ctx &X, int ri, int k0, const floatx16 &s, float m, float &l,
+                                         const uintx4 (&svf)[2][4], floatx16 (&o)[4])
+{
+    const int lim = ri - k0 - 4 * X.h; // the row sees keys 0..ri; element e holds key k0 + 8*(e/4) + e%4 + 4*h
+    unsigned pk[8];
+    float rs = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; e += 2) {
+        const float s0 = 8 * (e >> 2) + (e & 3) <= lim ? s[e] : -INFINITY;
+        const float s1 = 8 * ((e + 1) >> 2) + ((e + 1) & 3) <= lim ? s[e + 1] : -INFINITY;
+        const float p0 = fast_exp2(__builtin_fmaf(s0, X.c, -m));
+        const float p1 = fast_exp2(__builtin_fmaf(s1, X.c, -m));
+        rs += p0;
+        rs += p1;
+        pk[e >> 1] = pack_bf16(p0, p1);
+    }
+    l += rs;
+    pv_from_scratch(X, svf[0], as_bf16x8(uintx4{pk[0], pk[1], pk[2], pk[3]}), o);
+    pv_from_scratch(X, svf[1], as_bf16x8(uintx4{pk[4], pk[5], pk[6], pk[7]}), o);
+}
+
+// One step of the software pipeline.  On entry `s` holds the raw scores of the current tile;
+// the step computes the scores of the next tile (from LDS image `k_next`, or from the suffix K
+// fragments `skf` when NEXT_FROM_REGS), the weights of the current tile and its value product
+// from LDS image `v_cur`.  The eight score MFMAs are interleaved one to one with the weights
+// of two score elements each, and from the fifth on with the value MFMAs of the first 16 keys.
+// FRESH: the output accumulators start from zero here.
+template <bool FRESH, bool NEXT_FROM_REGS>
+__device__ __attribute__((always_inline)) void pipe_step(lds_u8 *k_next, const uintx4 (&skf)[8], lds_u8 *v_cur,
+                                                         const uintx4 (&q)[8], floatx16 &s, float c, float m,
+                                                         float &l, floatx16 (&o)[4])
+{
+    floatx16 sn;
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+        sn[e] = 0.f;
+    uintx4 kfr[8];
+    bf16x8 vfr[2][4];
+    unsigned pk[8];
+    bf16x8 pf0;
+    float rs = 0.f;
+    if (!NEXT_FROM_REGS) {
+        kfr[0] = *(lds_u128 *)(k_next);
+        kfr[1] = *(lds_u128 *)(k_next + 1024);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        // LDS reads for later steps: K two steps ahead, V(dt = ks%4, j = ks/4) four steps ahead
+        if (!NEXT_FROM_REGS && ks + 2 < 8)
+            kfr[ks + 2] = *(lds_u128 *)(k_next + (ks + 2) * 1024);
+        vfr[ks >> 2][ks & 3] = v_fragment(v_cur, ks & 3, ks >> 2);
+        // matrix cores
+        sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(NEXT_FROM_REGS ? skf[ks] : kfr[ks]), as_bf16x8(q[ks]),
+                                                     sn, 0, 0, 0);
+        if (ks >= 4) {
+            floatx16 acc = o[ks - 4];
+            if (FRESH) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    acc[e] = 0.f;
+            }
+            o[ks - 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[0][ks - 4], pf0, acc, 0, 0, 0);
+        }
+        // vector ALU: weights of elements 2ks and 2ks+1 of the current tile
+        const float p0 = fast_exp2(__builtin_fmaf(s[2 * ks], c, -m));
+        const float p1 = fast_exp2(__builtin_fmaf(s[2 * ks + 1], c, -m));
+        rs += p0;
+        rs += p1;
+        pk[ks] = pack_bf16(p0, p1);
+        if (ks == 3)
+            pf0 = as_bf16x8(uintx4{pk[0], pk[1], pk[2], pk[3]});
+        // Keep the step together: the empty asm makes this step's vector results exist here,
+        // and nothing may be moved across the barrier that follows it.
+        asm volatile("" : "+v"(rs), "+v"(pk[ks]));
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    const bf16x8 pf1 = as_bf16x8(uintx4{pk[4], pk[5], pk[6], pk[7]});
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[1][dt], pf1, o[dt], 0, 0, 0);
+    l += rs;
+    s = sn;
+}
+
+} // namespace
+} // namespace pskv

@@ -58,6 +58,10 @@ def test_tiny_f32_full(pk):
     (3, 300, 33, 5, 33, 14, 2),     # group 7 (28/4-style), odd sizes everywhere
     (2, 700, 70, 33, 70, 2, 2),     # suffix longer than one key tile
     (1, 64, 16, 16, 16, 1, 1),      # single candidate, single head
+    (3, 300, 32, 5, 32, 8, 2),      # streamed prefix, blocks inside one candidate, one suffix step
+    (9, 289, 32, 0, 32, 4, 1),      # ... ragged last prefix tile, last pass with idle wavefronts
+    (3, 420, 64, 20, 64, 2, 2),     # ... two suffix steps, second row block sometimes all padding
+    (2, 1000, 96, 1, 96, 3, 3),     # ... three suffix steps
 ])
 def test_small_shapes_bf16(pk, impl, B, P, S, lo, hi, Hq, Hkv):
     w = gen.custom_workload(f"small_{B}_{P}_{S}_{Hq}_{Hkv}", B, P, S, lo, hi, Hq, Hkv, 128, "bf16",
@@ -145,7 +149,9 @@ BF16_ONE, BF16_EIGHT = 0x3F80, 0x4100
 @pytest.mark.parametrize("B,P,S,lo,hi,Hq,Hkv", [
     (4, 256, 24, 16, 24, 8, 2),     # blocks inside one candidate, one suffix step: pipelined kernel
     (5, 100, 20, 20, 20, 4, 4),     # several candidates per block: general resident kernel
-    (3, 700, 40, 33, 40, 2, 2),     # long prefix: streaming kernel
+    (3, 700, 40, 33, 40, 2, 2),     # long prefix: general streaming kernel
+    (3, 700, 32, 20, 32, 8, 2),     # long prefix: pipelined streaming kernel, one suffix step
+    (3, 400, 64, 40, 64, 2, 2),     # ... several suffix steps
 ])
 def test_scores_far_above_the_first_tile(pk, impl, B, P, S, lo, hi, Hq, Hkv):
     """A late prefix key and a late suffix key whose scores exceed everything seen before by
