@@ -434,7 +434,7 @@ __device__ inline void suffix_classic(const Args &a, const Ctx &X, int r0, const
     }
 }
 
-// Suffix step with a fixed reference maximum m (pipelined kernels): raw scores s of the keys
+// Suffix step with a fixed reference maximum m (suffix steps after the first): raw scores s of the keys
 // k0..k0+31 of the row's own candidate, causal mask, weights, value product through the
 // scratch tile.
 __device__ inline void suffix_step_fixed(const Ctx &X, int ri, int k0, const floatx16 &s, float m, float &l,
@@ -458,67 +458,100 @@ __device__ inline void suffix_step_fixed(const Ctx &X, int ri, int k0, const flo
     pv_from_scratch(X, svf[1], as_bf16x8(uintx4{pk[4], pk[5], pk[6], pk[7]}), o);
 }
 
-// One step of the software pipeline.  On entry `s` holds the raw scores of the current tile;
-// the step computes the scores of the next tile (from LDS image `k_next`, or from the suffix K
-// fragments `skf` when NEXT_FROM_REGS), the weights of the current tile and its value product
-// from LDS image `v_cur`.  The eight score MFMAs are interleaved one to one with the weights
-// of two score elements each, and from the fifth on with the value MFMAs of the first 16 keys.
-// FRESH: the output accumulators start from zero here.
-template <bool FRESH, bool NEXT_FROM_REGS>
-__device__ __attribute__((always_inline)) void pipe_step(lds_u8 *k_next, const uintx4 (&skf)[8], lds_u8 *v_cur,
-                                                         const uintx4 (&q)[8], floatx16 &s, float c, float m,
-                                                         float &l, floatx16 (&o)[4])
+// Fragments 0 and 1 of the images a pipeline step starts with, read during the step before.
+struct Pre {
+    uintx4 k[2];
+    bf16x8 v[2];
+};
+
+// Sum of the two bf16 values packed in w, added to acc.
+__device__ inline float add_pair(unsigned w, float acc)
 {
-    floatx16 sn;
-#pragma unroll
-    for (int e = 0; e < 16; ++e)
-        sn[e] = 0.f;
+    bf16x2 a;
+    __builtin_memcpy(&a, &w, 4);
+    const bf16x2 one = {(__bf16)1.0f, (__bf16)1.0f};
+    return __builtin_amdgcn_fdot2_f32_bf16(a, one, acc, false);
+}
+
+// One tile step of the three-stage software pipeline.  With t the current tile, the step
+//   - computes the raw scores of tile t+1 into sn     (HAS_QK; K fragments from LDS image k_next,
+//                                                      or from the registers skf when FROM_REGS),
+//   - turns the raw scores s of tile t into weights   (relative to the fixed reference m; MASK:
+//     pc, packed bf16, and adds their sum to l         element e is visible iff its key offset
+//                                                      8*(e/4) + e%4 is <= lim),
+//   - adds tile t-1 to the output: O^T += V^T P^T     (HAS_PV; V image v_prev, weights pp;
+//                                                      FRESH: the accumulators start from zero).
+// Each of its eight sub-steps issues one score MFMA, one value MFMA and the vector work of two
+// score elements, so that matrix cores and vector ALU stay evenly loaded throughout; the row
+// sum is taken over the rounded weights, the ones the value product uses.  LDS fragments are
+// read two sub-steps ahead; fragments 0 and 1 of the images the following step starts with
+// (k_after when NEXT_K, v_cur when NEXT_V) are read during sub-steps 6 and 7 into `pre`.
+template <bool HAS_QK, bool FROM_REGS, bool HAS_PV, bool FRESH, bool MASK, bool NEXT_K, bool NEXT_V>
+__device__ __attribute__((always_inline)) void pipe_tile(lds_u8 *k_next, const uintx4 (&skf)[8], lds_u8 *v_prev,
+                                                         lds_u8 *k_after, lds_u8 *v_cur, Pre &pre,
+                                                         const uintx4 (&q)[8], const floatx16 &s, floatx16 &sn, float c,
+                                                         float m, int lim, float &l, const uintx4 (&pp)[2],
+                                                         uintx4 (&pc)[2], floatx16 (&o)[4])
+{
     uintx4 kfr[8];
-    bf16x8 vfr[2][4];
+    bf16x8 vfr[8];
     unsigned pk[8];
-    bf16x8 pf0;
     float rs = 0.f;
-    if (!NEXT_FROM_REGS) {
-        kfr[0] = *(lds_u128 *)(k_next);
-        kfr[1] = *(lds_u128 *)(k_next + 1024);
+    if (HAS_QK) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            sn[e] = 0.f;
+        if (!FROM_REGS) {
+            kfr[0] = pre.k[0];
+            kfr[1] = pre.k[1];
+        }
+    }
+    if (HAS_PV) {
+        vfr[0] = pre.v[0];
+        vfr[1] = pre.v[1];
     }
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-        // LDS reads for later steps: K two steps ahead, V(dt = ks%4, j = ks/4) four steps ahead
-        if (!NEXT_FROM_REGS && ks + 2 < 8)
+        // LDS reads for later sub-steps and for the following step
+        if (HAS_QK && !FROM_REGS && ks + 2 < 8)
             kfr[ks + 2] = *(lds_u128 *)(k_next + (ks + 2) * 1024);
-        vfr[ks >> 2][ks & 3] = v_fragment(v_cur, ks & 3, ks >> 2);
+        if (HAS_PV && ks + 2 < 8)
+            vfr[ks + 2] = v_fragment(v_prev, (ks + 2) & 3, (ks + 2) >> 2);
+        if (NEXT_K && ks >= 6)
+            pre.k[ks - 6] = *(lds_u128 *)(k_after + (ks - 6) * 1024);
+        if (NEXT_V && ks >= 6)
+            pre.v[ks - 6] = v_fragment(v_cur, ks - 6, 0);
         // matrix cores
-        sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(NEXT_FROM_REGS ? skf[ks] : kfr[ks]), as_bf16x8(q[ks]),
-                                                     sn, 0, 0, 0);
-        if (ks >= 4) {
-            floatx16 acc = o[ks - 4];
-            if (FRESH) {
+        if (HAS_QK)
+            sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(FROM_REGS ? skf[ks] : kfr[ks]), as_bf16x8(q[ks]), sn, 0,
+                                                         0, 0);
+        if (HAS_PV) {
+            floatx16 acc = o[ks & 3];
+            if (FRESH && ks < 4) {
 #pragma unroll
                 for (int e = 0; e < 16; ++e)
                     acc[e] = 0.f;
             }
-            o[ks - 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[0][ks - 4], pf0, acc, 0, 0, 0);
+            o[ks & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[ks], as_bf16x8(pp[ks >> 2]), acc, 0, 0, 0);
         }
         // vector ALU: weights of elements 2ks and 2ks+1 of the current tile
-        const float p0 = fast_exp2(__builtin_fmaf(s[2 * ks], c, -m));
-        const float p1 = fast_exp2(__builtin_fmaf(s[2 * ks + 1], c, -m));
-        rs += p0;
-        rs += p1;
+        float s0 = s[2 * ks], s1 = s[2 * ks + 1];
+        if (MASK) {
+            s0 = 8 * ((2 * ks) >> 2) + ((2 * ks) & 3) <= lim ? s0 : -INFINITY;
+            s1 = 8 * ((2 * ks + 1) >> 2) + ((2 * ks + 1) & 3) <= lim ? s1 : -INFINITY;
+        }
+        const float p0 = fast_exp2(__builtin_fmaf(s0, c, -m));
+        const float p1 = fast_exp2(__builtin_fmaf(s1, c, -m));
         pk[ks] = pack_bf16(p0, p1);
-        if (ks == 3)
-            pf0 = as_bf16x8(uintx4{pk[0], pk[1], pk[2], pk[3]});
-        // Keep the step together: the empty asm makes this step's vector results exist here,
-        // and nothing may be moved across the barrier that follows it.
+        rs = add_pair(pk[ks], rs);
+        // Keep the sub-step together: the empty asm makes its vector results exist here, and
+        // nothing may be moved across the barrier that follows it.
         asm volatile("" : "+v"(rs), "+v"(pk[ks]));
         __builtin_amdgcn_sched_barrier(0);
     }
-    const bf16x8 pf1 = as_bf16x8(uintx4{pk[4], pk[5], pk[6], pk[7]});
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfr[1][dt], pf1, o[dt], 0, 0, 0);
     l += rs;
-    s = sn;
+    pc[0] = uintx4{pk[0], pk[1], pk[2], pk[3]};
+    pc[1] = uintx4{pk[4], pk[5], pk[6], pk[7]};
 }
 
 } // namespace

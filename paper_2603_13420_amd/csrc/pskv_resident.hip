@@ -111,7 +111,7 @@ void resident_general_kernel(Args a, int wgs_per_head, int ntiles)
 // ------------------------------------------------------------------------------------------
 // Pipelined path.  Preconditions (checked by the launcher): S*G is a multiple of 32, so a
 // 32-row block lies inside one candidate; S <= 32, so the suffix is one 32-key step; and the
-// prefix has at least two tiles.
+// prefix has at least three tiles.
 //
 // Softmax without per-tile maxima: the first prefix tile fixes the row's reference maximum;
 // later tiles take exp2 relative to it whatever their own maximum is (a larger score just gives
@@ -130,7 +130,9 @@ void resident_pipelined_kernel(Args a, int wgs_per_head, int ntiles)
     const Ctx X = make_ctx(a, smem, ntiles, tid, head);
     const int nblocks = (X.Mtot + kBlockRows - 1) / kBlockRows;
     const int blk_stride = wgs_per_head * kNW;
-    const int rows_per_cand = a.S * a.G; // a multiple of 32
+    const int T = ntiles;
+    auto kimg = [&](int t) { return X.k_lane + t * kTileBytes; };
+    auto vimg = [&](int t) { return X.v_lane + t * kTileBytes; };
 
     // First key a block's rows can see and last suffix position its rows have, from its index:
     // block blk covers rows [32*blk, 32*blk+31] of candidate 32*blk / (S*G).
@@ -173,36 +175,57 @@ void resident_pipelined_kernel(Args a, int wgs_per_head, int ntiles)
         load_suffix_k(a, X, sb, 0, skmax, skf);
 
         // ---- first prefix tile: scores, reference maximum ----
-        floatx16 s;
+        floatx16 sA, sB; // raw scores of the current and of the next tile, roles alternating
 #pragma unroll
         for (int e = 0; e < 16; ++e)
-            s[e] = 0.f;
+            sA[e] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks)
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*(lds_u128 *)(X.k_lane + ks * 1024)), as_bf16x8(q[ks]), s,
-                                                        0, 0, 0);
-        float m = s[0];
+            sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*(lds_u128 *)(X.k_lane + ks * 1024)), as_bf16x8(q[ks]),
+                                                         sA, 0, 0, 0);
+        Pre pre;
+        pre.k[0] = *(lds_u128 *)(kimg(1));
+        pre.k[1] = *(lds_u128 *)(kimg(1) + 1024);
+        float m = sA[0];
 #pragma unroll
         for (int e = 1; e < 16; ++e)
-            m = fmaxf(m, s[e]);
+            m = fmaxf(m, sA[e]);
         m = fmaxf(m, __shfl_xor(m, 32, 64)) * X.c; // the other half-wave holds the other 16 keys
         float l = 0.f;
         floatx16 o[4];
+        uintx4 pA[2], pB[2]; // packed weights of the current and of the previous tile, roles alternating
 
-        // ---- pipeline over the prefix tiles: scores of tile kt+1 under the weights of tile kt ----
-        pipe_step<true, false>(X.k_lane + kTileBytes, skf, X.v_lane, q, s, X.c, m, l, o);
-        for (int kt = 1; kt < ntiles - 1; ++kt)
-            pipe_step<false, false>(X.k_lane + (kt + 1) * kTileBytes, skf, X.v_lane + kt * kTileBytes, q, s, X.c, m, l, o);
+        // ---- pipeline over the prefix tiles: step t = scores of tile t+1, weights of tile t,
+        //      value product of tile t-1 ----
+        pipe_tile<true, false, false, false, false, true, true>(kimg(1), skf, vimg(0), kimg(2), vimg(0), pre, q, sA, sB,
+                                                                X.c, m, 0, l, pA, pA, o);
+        pipe_tile<true, false, true, true, false, true, true>(kimg(2), skf, vimg(0), kimg(3 < T ? 3 : T - 1), vimg(1), pre,
+                                                              q, sB, sA, X.c, m, 0, l, pA, pB, o);
+        int t = 2;
+        for (; t + 1 <= T - 2; t += 2) {
+            pipe_tile<true, false, true, false, false, true, true>(kimg(t + 1), skf, vimg(t - 1), kimg(t + 2), vimg(t), pre,
+                                                                   q, sA, sB, X.c, m, 0, l, pB, pA, o);
+            pipe_tile<true, false, true, false, false, true, true>(kimg(t + 2), skf, vimg(t), kimg(t + 3 < T ? t + 3 : T - 1),
+                                                                   vimg(t + 1), pre, q, sB, sA, X.c, m, 0, l, pA, pB, o);
+        }
+        if (t <= T - 2) { // one step left over: do it and put scores and weights back in their places
+            pipe_tile<true, false, true, false, false, true, true>(kimg(t + 1), skf, vimg(t - 1), kimg(T - 1), vimg(t), pre,
+                                                                   q, sA, sB, X.c, m, 0, l, pB, pA, o);
+            sA = sB;
+            pB[0] = pA[0];
+            pB[1] = pA[1];
+        }
         if (a.P & (kTileKeys - 1)) { // ragged last prefix tile: keys past the prefix are not visible
-            const int nv = a.P - (ntiles - 1) * kTileKeys - 4 * X.h;
+            const int nv = a.P - (T - 1) * kTileKeys - 4 * X.h;
 #pragma unroll
             for (int e = 0; e < 16; ++e)
                 if (8 * (e >> 2) + (e & 3) >= nv)
-                    s[e] = -INFINITY;
+                    sA[e] = -INFINITY;
         }
-        load_suffix_v(a, X, sb, 0, skmax, svf); // one tile ahead of its use
+        load_suffix_v(a, X, sb, 0, skmax, svf); // one step ahead of its use
         // ---- last prefix tile: the "next scores" are the suffix scores, from the K registers ----
-        pipe_step<false, true>(X.k_lane, skf, X.v_lane + (ntiles - 1) * kTileBytes, q, s, X.c, m, l, o);
+        pipe_tile<true, true, true, false, false, false, true>(kimg(0), skf, vimg(T - 2), kimg(0), vimg(T - 1), pre, q, sA,
+                                                               sB, X.c, m, 0, l, pB, pA, o);
 
         // Q has been used for the last time: the next block's row decode and Q take its place.
         // (Requested unconditionally, for a clamped block index past the end: a load under a
@@ -211,8 +234,13 @@ void resident_pipelined_kernel(Args a, int wgs_per_head, int ntiles)
         nxt = decode_row(a, X, blk < nblocks ? blk : nblocks - 1);
         load_q(a, X, nxt, q);
 
-        // ---- suffix step: causal mask, weights, value product through the scratch tile ----
-        suffix_step_fixed(X, (int)row.ri, 0, s, m, l, svf, o);
+        // ---- suffix step: causal mask and weights under the value product of the last prefix
+        //      tile; then the suffix value product through the scratch tile ----
+        // the row sees keys 0..ri; element e holds key 8*(e/4) + e%4 + 4*h
+        pipe_tile<false, false, true, false, true, false, false>(kimg(0), skf, vimg(T - 1), kimg(0), vimg(0), pre, q, sB, sB,
+                                                                 X.c, m, (int)row.ri - 4 * X.h, l, pA, pB, o);
+        pv_from_scratch(X, svf[0], as_bf16x8(pB[0]), o);
+        pv_from_scratch(X, svf[1], as_bf16x8(pB[1]), o);
 
         any_bad |= __builtin_amdgcn_ballot_w64(rvalid && !(l < kBig)) != 0;
         store_block(a, X, r0, row, rvalid, m, l, o);
@@ -262,7 +290,7 @@ hipError_t launch_resident(const Args &a, hipStream_t stream)
         per_head = useful;
     const unsigned grid = (unsigned)(per_head * a.Hkv);
     const size_t lds = (size_t)2 * ntiles * kTileBytes + kNW * kScrBytes;
-    const bool pipelined = ((long long)a.S * a.G) % kBlockRows == 0 && a.S <= kTileKeys && ntiles >= 2;
+    const bool pipelined = ((long long)a.S * a.G) % kBlockRows == 0 && a.S <= kTileKeys && ntiles >= 3;
     if (pipelined)
         hipLaunchKernelGGL(resident_pipelined_kernel, dim3(grid), dim3(kNW * 64), lds, stream, a, (int)per_head, ntiles);
     else

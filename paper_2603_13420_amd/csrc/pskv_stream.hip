@@ -25,10 +25,9 @@
 namespace pskv {
 namespace {
 
-constexpr int kRing = 4;                   // tile slots in LDS
+constexpr int kRing = 8;                   // tile slots in LDS
 constexpr int kSlotBytes = 2 * kTileBytes; // K image, then V image
-constexpr int kFlagBytes = 64;             // one int per wavefront
-constexpr int kLdsBytes = kRing * kSlotBytes + kNW * kScrBytes + kFlagBytes;
+constexpr int kLdsBytes = kRing * kSlotBytes + kNW * kScrBytes;
 constexpr int kPassRows = kNW * kBlockRows;
 
 typedef __attribute__((address_space(3))) int lds_int;
@@ -146,35 +145,70 @@ void stream_general_kernel(Args a, int npasses, int ntiles)
 
 // ------------------------------------------------------------------------------------------
 // Pipelined passes.  Preconditions (checked by the launcher): S*G is a multiple of 32, so a
-// 32-row block lies inside one candidate, and the prefix has at least four tiles.
+// 32-row block lies inside one candidate; the prefix has at least six tiles; one head's prefix
+// spans less than 2^31 bytes, so tile addresses are a scalar base plus a 32-bit lane offset.
 // ONE_STEP: S <= 32, the suffix is a single 32-key step.
 //
-// Ring protocol.  Iteration kt of a pass uses the K image of tile kt+1 and the V image of
-// tile kt.  At its top every thread writes its chunks of tile kt+2 (fetched one iteration
-// earlier) into slot (kt+2) % 4, requests tile kt+3, and the workgroup meets at a barrier.
-// The slot written at the top of iteration kt last held tile kt-2, which was last read in
-// iteration kt-2; the barrier at the top of iteration kt-1 was passed only by wavefronts that
-// had finished that iteration.  A tile written at the top of iteration kt is first read in
-// iteration kt+1, after the barrier of iteration kt.
+// Ring protocol.  Step t of a pass (see pipe_tile) reads the K images of tiles t+1 and t+2 and
+// the V images of tiles t-1 and t.  Steps are taken two at a time.  At the top of the pair
+// (t, t+1) every thread writes its chunks of tiles t+2 and t+3 (fetched during the pair before)
+// into slots (t+2) % 8 and (t+3) % 8, requests tiles t+4 and t+5, and the workgroup meets at a
+// barrier; the pair then reads tiles t-1 .. t+3.  The slots written last held tiles t-6 and
+// t-5; a wavefront that has not reached this barrier yet is inside the pair before, which reads
+// nothing older than tile t-3.  Tile indices past the last tile are clamped to it: such a
+// write puts a copy of the last tile into a slot that no step reads any more.
+// Rows past the end of a ragged last tile are fetched from the last prefix row instead: their
+// scores are masked and their weights are exactly zero, so finite data is all that is needed.
 // ------------------------------------------------------------------------------------------
+struct Stager {
+    const unsigned char *kbase, *vbase; // this head's prefix K and V (wave-uniform)
+    unsigned k_off, v_off;              // this thread's chunk within a full tile, bytes
+    unsigned k_off_last, v_off_last;    // ... within the last tile (rows clamped into the prefix)
+    unsigned tile_stride;               // bytes from one tile to the next
+    int last;                           // index of the last tile
+};
+
+__device__ inline void stage_load(const Stager &g, int kt, uintx4 &kv, uintx4 &vv)
+{
+    const int ktc = kt < g.last ? kt : g.last;
+    const unsigned base = (unsigned)ktc * g.tile_stride;
+    const unsigned ko = base + (ktc == g.last ? g.k_off_last : g.k_off);
+    const unsigned vo = base + (ktc == g.last ? g.v_off_last : g.v_off);
+    kv = *reinterpret_cast<const uintx4 *>(g.kbase + ko);
+    vv = *reinterpret_cast<const uintx4 *>(g.vbase + vo);
+}
+
 template <bool ONE_STEP>
 __global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
 void stream_pipelined_kernel(Args a, int npasses, int ntiles)
 {
     extern __shared__ __align__(16) unsigned char smem_generic[];
     lds_u8 *smem = (lds_u8 *)smem_generic;
-    lds_int *flags = (lds_int *)(smem + kRing * kSlotBytes + kNW * kScrBytes);
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     Ctx X = make_stream_ctx(a, smem, tid);
     const int nblocks = (X.Mtot + kBlockRows - 1) / kBlockRows;
-    const TileSlot t = make_tile_slot(tid);
-    auto k_slot = [&](int kt) { return X.k_lane + (kt & (kRing - 1)) * kSlotBytes; };
-    auto v_slot = [&](int kt) { return X.v_lane + (kt & (kRing - 1)) * kSlotBytes; };
+    const int T = ntiles;
+    auto kimg = [&](int t) { return X.k_lane + (t & (kRing - 1)) * kSlotBytes; };
+    auto vimg = [&](int t) { return X.v_lane + (t & (kRing - 1)) * kSlotBytes; };
     auto stage_write = [&](int kt, const uintx4 &kv, const uintx4 &vv) {
-        lds_u8 *slot = smem + (kt & (kRing - 1)) * kSlotBytes;
-        write_tile_chunks(a, t, kt, slot, slot + kTileBytes, tid, kv, vv);
+        lds_u8 *slot = smem + (kt & (kRing - 1)) * kSlotBytes + tid * 16;
+        *(lds_u128 *)slot = kv;
+        *(lds_u128 *)(slot + kTileBytes) = vv;
     };
+
+    Stager g;
+    {
+        const TileSlot ts = make_tile_slot(tid);
+        const int nlast = a.P - (T - 1) * kTileKeys; // rows of the last tile, 1..32
+        const int kr = ts.k_row < nlast ? ts.k_row : nlast - 1, vr = ts.v_row < nlast ? ts.v_row : nlast - 1;
+        g.k_off = (unsigned)(ts.k_row * a.kp_sp + ts.k_chunk * 8) * 2u;
+        g.v_off = (unsigned)(ts.v_row * a.kp_sp + ts.v_chunk * 8) * 2u;
+        g.k_off_last = (unsigned)(kr * a.kp_sp + ts.k_chunk * 8) * 2u;
+        g.v_off_last = (unsigned)(vr * a.kp_sp + ts.v_chunk * 8) * 2u;
+        g.tile_stride = (unsigned)(kTileKeys * a.kp_sp) * 2u;
+        g.last = T - 1;
+    }
 
     bool wg_bad = false;
     int p = blockIdx.x;
@@ -185,24 +219,29 @@ void stream_pipelined_kernel(Args a, int npasses, int ntiles)
 
     while (p < npasses) {
         set_head(a, X, ps.head);
-        const unsigned short *kpg = reinterpret_cast<const unsigned short *>(a.kp) + (long long)ps.head * a.kp_sh;
-        const unsigned short *vpg = reinterpret_cast<const unsigned short *>(a.vp) + (long long)ps.head * a.kp_sh;
+        g.kbase = reinterpret_cast<const unsigned char *>(a.kp) + (long long)ps.head * a.kp_sh * 2;
+        g.vbase = reinterpret_cast<const unsigned char *>(a.vp) + (long long)ps.head * a.kp_sh * 2;
         const int blk = ps.blk, r0 = blk * kBlockRows;
         const bool active = ps.active;
         const Row row = nxt;
         const bool rvalid = active && row.rin && (int)row.ri < clamp_len(a, row.rlen);
 
-        // the ring is free here: the barrier that ended the previous pass was passed only by
-        // wavefronts that had finished reading it
-        uintx4 kv, vv;
+        // The ring is free here: the barrier that ended the previous pass was passed only by
+        // wavefronts that had finished reading it.  Tiles 0..3 go in at once.
+        uintx4 kv0, vv0, kv1, vv1;
         {
-            uintx4 kv0, vv0;
-            load_tile_chunks(a, kpg, vpg, t, 0, kv0, vv0);
-            load_tile_chunks(a, kpg, vpg, t, 1, kv, vv);
+            uintx4 kv2, vv2, kv3, vv3;
+            stage_load(g, 0, kv0, vv0);
+            stage_load(g, 1, kv1, vv1);
+            stage_load(g, 2, kv2, vv2);
+            stage_load(g, 3, kv3, vv3);
             stage_write(0, kv0, vv0);
-            stage_write(1, kv, vv);
+            stage_write(1, kv1, vv1);
+            stage_write(2, kv2, vv2);
+            stage_write(3, kv3, vv3);
         }
-        load_tile_chunks(a, kpg, vpg, t, 2, kv, vv);
+        stage_load(g, 4, kv0, vv0);
+        stage_load(g, 5, kv1, vv1);
         __syncthreads();
 
         // the block's suffix: candidate sb, keys 0..skmax
@@ -212,50 +251,82 @@ void stream_pipelined_kernel(Args a, int npasses, int ntiles)
         const int skmax = i_hi < len - 1 ? i_hi : len - 1;
 
         // ---- first prefix tile: scores, reference maximum ----
-        floatx16 s;
+        floatx16 sA, sB; // raw scores of the current and of the next tile, roles alternating
 #pragma unroll
         for (int e = 0; e < 16; ++e)
-            s[e] = 0.f;
+            sA[e] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks)
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*(lds_u128 *)(k_slot(0) + ks * 1024)), as_bf16x8(q[ks]),
-                                                        s, 0, 0, 0);
-        float m = s[0];
+            sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*(lds_u128 *)(kimg(0) + ks * 1024)), as_bf16x8(q[ks]), sA,
+                                                         0, 0, 0);
+        Pre pre;
+        pre.k[0] = *(lds_u128 *)(kimg(1));
+        pre.k[1] = *(lds_u128 *)(kimg(1) + 1024);
+        float m = sA[0];
 #pragma unroll
         for (int e = 1; e < 16; ++e)
-            m = fmaxf(m, s[e]);
+            m = fmaxf(m, sA[e]);
         m = fmaxf(m, __shfl_xor(m, 32, 64)) * X.c; // the other half-wave holds the other 16 keys
         float l = 0.f;
         floatx16 o[4];
+        uintx4 pA[2], pB[2]; // packed weights of the current and of the previous tile, roles alternating
         uintx4 skf[8], svf[2][4];
 
-        // ---- pipeline over the prefix tiles: scores of tile kt+1 under the weights of tile kt ----
-        stage_write(2, kv, vv);
-        load_tile_chunks(a, kpg, vpg, t, 3, kv, vv);
-        __syncthreads();
-        pipe_step<true, false>(k_slot(1), skf, v_slot(0), q, s, X.c, m, l, o);
-        for (int kt = 1; kt < ntiles - 3; ++kt) {
-            stage_write(kt + 2, kv, vv);
-            load_tile_chunks(a, kpg, vpg, t, kt + 3, kv, vv);
+        // ---- pipeline over the prefix tiles: step t = scores of tile t+1, weights of tile t,
+        //      value product of tile t-1 ----
+        pipe_tile<true, false, false, false, false, true, true>(kimg(1), skf, vimg(0), kimg(2), vimg(0), pre, q, sA, sB,
+                                                                X.c, m, 0, l, pA, pA, o);
+        pipe_tile<true, false, true, true, false, true, true>(kimg(2), skf, vimg(0), kimg(3), vimg(1), pre, q, sB, sA, X.c,
+                                                              m, 0, l, pA, pB, o);
+        // one pair of steps
+#define PSKV_STEP_PAIR(t)                                                                                              \
+    do {                                                                                                               \
+        pipe_tile<true, false, true, false, false, true, true>(kimg((t) + 1), skf, vimg((t) - 1), kimg((t) + 2),       \
+                                                               vimg(t), pre, q, sA, sB, X.c, m, 0, l, pB, pA, o);      \
+        pipe_tile<true, false, true, false, false, true, true>(kimg((t) + 2), skf, vimg(t),                            \
+                                                               kimg((t) + 3 < T ? (t) + 3 : T - 1), vimg((t) + 1),     \
+                                                               pre, q, sB, sA, X.c, m, 0, l, pA, pB, o);               \
+    } while (0)
+        int t = 2;
+        for (; t + 3 <= T - 2; t += 2) { // tiles t+2, t+3 into the ring, tiles t+4, t+5 requested, barrier
+            stage_write(t + 2, kv0, vv0);
+            stage_write(t + 3, kv1, vv1);
+            stage_load(g, t + 4, kv0, vv0);
+            stage_load(g, t + 5, kv1, vv1);
             __syncthreads();
-            pipe_step<false, false>(k_slot(kt + 1), skf, v_slot(kt), q, s, X.c, m, l, o);
+            PSKV_STEP_PAIR(t);
         }
-        stage_write(ntiles - 1, kv, vv);
-        __syncthreads();
-        // no more tile fetches behind which these would queue; two iterations ahead of their use
-        load_suffix_k(a, X, sb, 0, skmax, skf);
-        pipe_step<false, false>(k_slot(ntiles - 2), skf, v_slot(ntiles - 3), q, s, X.c, m, l, o);
-        pipe_step<false, false>(k_slot(ntiles - 1), skf, v_slot(ntiles - 2), q, s, X.c, m, l, o);
+        // The last pair requests no further tiles; the suffix K fragments, needed two or three
+        // steps from here, are requested once the staging registers are free.
+        if (t + 1 <= T - 2) {
+            stage_write(t + 2, kv0, vv0);
+            stage_write(t + 3, kv1, vv1);
+            load_suffix_k(a, X, sb, 0, skmax, skf);
+            __syncthreads();
+            PSKV_STEP_PAIR(t);
+            t += 2;
+        } else {
+            load_suffix_k(a, X, sb, 0, skmax, skf);
+        }
+#undef PSKV_STEP_PAIR
+        if (t <= T - 2) { // one step left over: do it and put scores and weights back in their places
+            pipe_tile<true, false, true, false, false, true, true>(kimg(t + 1), skf, vimg(t - 1), kimg(T - 1), vimg(t), pre,
+                                                                   q, sA, sB, X.c, m, 0, l, pB, pA, o);
+            sA = sB;
+            pB[0] = pA[0];
+            pB[1] = pA[1];
+        }
         if (a.P & (kTileKeys - 1)) { // ragged last prefix tile: keys past the prefix are not visible
-            const int nv = a.P - (ntiles - 1) * kTileKeys - 4 * X.h;
+            const int nv = a.P - (T - 1) * kTileKeys - 4 * X.h;
 #pragma unroll
             for (int e = 0; e < 16; ++e)
                 if (8 * (e >> 2) + (e & 3) >= nv)
-                    s[e] = -INFINITY;
+                    sA[e] = -INFINITY;
         }
-        load_suffix_v(a, X, sb, 0, skmax, svf);
+        load_suffix_v(a, X, sb, 0, skmax, svf); // one step ahead of its use
         // ---- last prefix tile: the "next scores" are those of the first suffix step ----
-        pipe_step<false, true>(k_slot(0), skf, v_slot(ntiles - 1), q, s, X.c, m, l, o);
+        pipe_tile<true, true, true, false, false, false, true>(kimg(0), skf, vimg(T - 2), kimg(0), vimg(T - 1), pre, q, sA,
+                                                               sB, X.c, m, 0, l, pB, pA, o);
 
         // the next pass of this workgroup (clamped past the end: requested unconditionally)
         p += gridDim.x;
@@ -265,19 +336,23 @@ void stream_pipelined_kernel(Args a, int npasses, int ntiles)
             load_q(a, X, nxt, q);
         }
 
-        // ---- suffix: causal mask, weights, value product through the scratch tile ----
-        suffix_step_fixed(X, (int)row.ri, 0, s, m, l, svf, o);
+        // ---- first suffix step: causal mask and weights under the value product of the last
+        //      prefix tile; then its own value product through the scratch tile ----
+        pipe_tile<false, false, true, false, true, false, false>(kimg(0), skf, vimg(T - 1), kimg(0), vimg(0), pre, q, sB, sB,
+                                                                 X.c, m, (int)row.ri - 4 * X.h, l, pA, pB, o);
+        pv_from_scratch(X, svf[0], as_bf16x8(pB[0]), o);
+        pv_from_scratch(X, svf[1], as_bf16x8(pB[1]), o);
         if (!ONE_STEP) {
             for (int k0 = kTileKeys; k0 <= skmax; k0 += kTileKeys) {
                 load_suffix_k(a, X, sb, k0, skmax, skf);
                 load_suffix_v(a, X, sb, k0, skmax, svf);
 #pragma unroll
                 for (int e = 0; e < 16; ++e)
-                    s[e] = 0.f;
+                    sB[e] = 0.f;
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks)
-                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(skf[ks]), as_bf16x8(q[ks]), s, 0, 0, 0);
-                suffix_step_fixed(X, (int)row.ri, k0, s, m, l, svf, o);
+                    sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(skf[ks]), as_bf16x8(q[ks]), sB, 0, 0, 0);
+                suffix_step_fixed(X, (int)row.ri, k0, sB, m, l, svf, o);
             }
             nxt = decode_row(a, X, ps.blk, ps.head);
             load_q(a, X, nxt, q);
@@ -286,10 +361,12 @@ void stream_pipelined_kernel(Args a, int npasses, int ntiles)
         const bool bad = __builtin_amdgcn_ballot_w64(rvalid && !(l < kBig)) != 0;
         if (active)
             store_block(a, X, r0, row, rvalid, m, l, o);
+        // the wavefront's verdict goes into the first word of its own scratch tile
         if (X.lane == 0)
-            flags[wave] = bad ? 1 : 0;
-        __syncthreads(); // ends the pass: the ring is free, the flags are visible
-        wg_bad |= __builtin_amdgcn_ballot_w64(flags[X.lane & (kNW - 1)] != 0) != 0;
+            *(lds_int *)X.scr = bad ? 1 : 0;
+        __syncthreads(); // ends the pass: the ring is free, the verdicts are visible
+        wg_bad |= __builtin_amdgcn_ballot_w64(*(lds_int *)(smem + kRing * kSlotBytes + (X.lane & (kNW - 1)) * kScrBytes) !=
+                                              0) != 0;
     }
 
     // Rare: some row met scores far above its first tile's maximum.  Whatever this workgroup
@@ -353,7 +430,8 @@ hipError_t launch_stream(const Args &a, hipStream_t stream)
     const long long rows = (long long)a.B * a.S * a.G;
     const long long npasses = ((rows + kPassRows - 1) / kPassRows) * a.Hkv;
     const unsigned grid = (unsigned)(npasses < num_cu ? npasses : num_cu);
-    const bool pipelined = ((long long)a.S * a.G) % kBlockRows == 0 && ntiles >= 4;
+    const bool pipelined = ((long long)a.S * a.G) % kBlockRows == 0 && ntiles >= 6 &&
+                           (long long)a.P * a.kp_sp * 2 < 0x7fffffffLL;
     if (!pipelined)
         hipLaunchKernelGGL(stream_general_kernel, dim3(grid), dim3(kNW * 64), kLdsBytes, stream, a, (int)npasses, ntiles);
     else if (a.S <= kTileKeys)
