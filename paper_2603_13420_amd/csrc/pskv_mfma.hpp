@@ -304,7 +304,9 @@ __device__ inline void store_block(const Args &a, const Ctx &X, int r0, const Ro
             const int rl = 8 * u + (X.lane >> 3);
             const uintx4 v = *(lds_u128 *)(X.scr + rl * 128 + (((X.lane & 7) ^ (rl & 7)) << 4));
             if (dst_ok[u])
-                *reinterpret_cast<uintx4 *>(dst[u] + 64 * pass) = v;
+                // the output is written once and not read again here: streaming stores keep it
+                // from piling up in L2, where it would wait for the write-back at the kernel's end
+                __builtin_nontemporal_store(v, reinterpret_cast<uintx4 *>(dst[u] + 64 * pass));
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -323,7 +325,7 @@ __device__ inline void store_zero_block(const Args &a, const Ctx &X, const Row &
                            (long long)row.ri * a.o_ss + (long long)row.rh * a.o_sh;
 #pragma unroll
     for (int u = 0; u < 8; ++u)
-        *reinterpret_cast<uintx4 *>(orow + 64 * X.h + 8 * u) = uintx4{0, 0, 0, 0};
+        __builtin_nontemporal_store(uintx4{0, 0, 0, 0}, reinterpret_cast<uintx4 *>(orow + 64 * X.h + 8 * u));
     if (a.lse && X.h == 0)
         a.lse[((long long)row.rb * a.Hq + row.rh) * a.S + row.ri] = -INFINITY;
 }
@@ -459,19 +461,11 @@ __device__ inline void suffix_step_fixed(const Ctx &X, int ri, int k0, const flo
 }
 
 // Fragments 0 and 1 of the images a pipeline step starts with, read during the step before.
+constexpr int kDist = 2; // LDS fragments are read this many sub-steps before their use
 struct Pre {
-    uintx4 k[2];
-    bf16x8 v[2];
+    uintx4 k[kDist];
+    bf16x8 v[kDist];
 };
-
-// Sum of the two bf16 values packed in w, added to acc.
-__device__ inline float add_pair(unsigned w, float acc)
-{
-    bf16x2 a;
-    __builtin_memcpy(&a, &w, 4);
-    const bf16x2 one = {(__bf16)1.0f, (__bf16)1.0f};
-    return __builtin_amdgcn_fdot2_f32_bf16(a, one, acc, false);
-}
 
 // One tile step of the three-stage software pipeline.  With t the current tile, the step
 //   - computes the raw scores of tile t+1 into sn     (HAS_QK; K fragments from LDS image k_next,
@@ -482,9 +476,9 @@ __device__ inline float add_pair(unsigned w, float acc)
 //   - adds tile t-1 to the output: O^T += V^T P^T     (HAS_PV; V image v_prev, weights pp;
 //                                                      FRESH: the accumulators start from zero).
 // Each of its eight sub-steps issues one score MFMA, one value MFMA and the vector work of two
-// score elements, so that matrix cores and vector ALU stay evenly loaded throughout; the row
-// sum is taken over the rounded weights, the ones the value product uses.  LDS fragments are
-// read two sub-steps ahead; fragments 0 and 1 of the images the following step starts with
+// score elements, so that matrix cores and vector ALU stay evenly loaded throughout.  (The row
+// sum uses plain additions: next to MFMA work the bf16 dot-product instruction costs several
+// times more issue time than two additions.)  LDS fragments are read two sub-steps ahead; the first fragments of the images the following step starts with
 // (k_after when NEXT_K, v_cur when NEXT_V) are read during sub-steps 6 and 7 into `pre`.
 template <bool HAS_QK, bool FROM_REGS, bool HAS_PV, bool FRESH, bool MASK, bool NEXT_K, bool NEXT_V>
 __device__ __attribute__((always_inline)) void pipe_tile(lds_u8 *k_next, const uintx4 (&skf)[8], lds_u8 *v_prev,
@@ -502,25 +496,27 @@ __device__ __attribute__((always_inline)) void pipe_tile(lds_u8 *k_next, const u
         for (int e = 0; e < 16; ++e)
             sn[e] = 0.f;
         if (!FROM_REGS) {
-            kfr[0] = pre.k[0];
-            kfr[1] = pre.k[1];
+#pragma unroll
+            for (int i = 0; i < kDist; ++i)
+                kfr[i] = pre.k[i];
         }
     }
     if (HAS_PV) {
-        vfr[0] = pre.v[0];
-        vfr[1] = pre.v[1];
+#pragma unroll
+        for (int i = 0; i < kDist; ++i)
+            vfr[i] = pre.v[i];
     }
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
         // LDS reads for later sub-steps and for the following step
-        if (HAS_QK && !FROM_REGS && ks + 2 < 8)
-            kfr[ks + 2] = *(lds_u128 *)(k_next + (ks + 2) * 1024);
-        if (HAS_PV && ks + 2 < 8)
-            vfr[ks + 2] = v_fragment(v_prev, (ks + 2) & 3, (ks + 2) >> 2);
-        if (NEXT_K && ks >= 6)
-            pre.k[ks - 6] = *(lds_u128 *)(k_after + (ks - 6) * 1024);
-        if (NEXT_V && ks >= 6)
-            pre.v[ks - 6] = v_fragment(v_cur, ks - 6, 0);
+        if (HAS_QK && !FROM_REGS && ks + kDist < 8)
+            kfr[ks + kDist] = *(lds_u128 *)(k_next + (ks + kDist) * 1024);
+        if (HAS_PV && ks + kDist < 8)
+            vfr[ks + kDist] = v_fragment(v_prev, (ks + kDist) & 3, (ks + kDist) >> 2);
+        if (NEXT_K && ks >= 8 - kDist)
+            pre.k[ks - (8 - kDist)] = *(lds_u128 *)(k_after + (ks - (8 - kDist)) * 1024);
+        if (NEXT_V && ks >= 8 - kDist)
+            pre.v[ks - (8 - kDist)] = v_fragment(v_cur, ks - (8 - kDist), 0);
         // matrix cores
         if (HAS_QK)
             sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(FROM_REGS ? skf[ks] : kfr[ks]), as_bf16x8(q[ks]), sn, 0,
@@ -543,7 +539,8 @@ __device__ __attribute__((always_inline)) void pipe_tile(lds_u8 *k_next, const u
         const float p0 = fast_exp2(__builtin_fmaf(s0, c, -m));
         const float p1 = fast_exp2(__builtin_fmaf(s1, c, -m));
         pk[ks] = pack_bf16(p0, p1);
-        rs = add_pair(pk[ks], rs);
+        rs += p0;
+        rs += p1;
         // Keep the sub-step together: the empty asm makes its vector results exist here, and
         // nothing may be moved across the barrier that follows it.
         asm volatile("" : "+v"(rs), "+v"(pk[ks]));

@@ -260,8 +260,9 @@ void stream_pipelined_kernel(Args a, int npasses, int ntiles)
             sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*(lds_u128 *)(kimg(0) + ks * 1024)), as_bf16x8(q[ks]), sA,
                                                          0, 0, 0);
         Pre pre;
-        pre.k[0] = *(lds_u128 *)(kimg(1));
-        pre.k[1] = *(lds_u128 *)(kimg(1) + 1024);
+#pragma unroll
+        for (int i = 0; i < kDist; ++i)
+            pre.k[i] = *(lds_u128 *)(kimg(1) + i * 1024);
         float m = sA[0];
 #pragma unroll
         for (int e = 1; e < 16; ++e)
