@@ -151,3 +151,125 @@ int pskv_oracle_attn(int B, int S, int P, int Hq, int Hkv, int D, int dtype, dou
     }
     return failed ? 2 : 0;
 }
+
+/*
+ * Batched multi-instruction form (paper Sec. 4.3, suffix-centric alignment; App. F.1, position
+ * consistency under padding): Np instructions, each with its own prefix K/V, LEFT-padded to a
+ * common Pp rows (the real rows of instruction n are the last pre_len[n] ones), and C
+ * consecutive candidates per instruction (candidate b belongs to instruction b / C, B = Np*C).
+ * A candidate attends to the real prefix rows of its own instruction and causally to its own
+ * suffix rows; padding rows of the prefix are excluded from attention (they may hold anything).
+ *
+ * Same plain procedure as above: for every candidate and KV head the real prefix rows of the
+ * candidate's instruction are physically copied into a private buffer (one prefix cache per
+ * instruction, repeated over its candidates the Standard-KV way), the suffix rows are appended
+ * and every valid query runs the max-subtracted softmax of Eq. 2 over the rows it may see.
+ *
+ * Layouts: k_pre,v_pre [Np,Pp,Hkv,D]; pre_len [Np] (NULL: every prefix has Pp real rows);
+ * the rest as for pskv_oracle_attn.  probs (optional) is [B,Hq,S,Pp+S]: column j < Pp is the
+ * padded prefix index j (0 on padding), column Pp+t is suffix token t.
+ */
+int pskv_oracle_attn_multi(int Np, int C, int S, int Pp, int Hq, int Hkv, int D, int dtype, double scale,
+                           const void *q, const void *k_suf, const void *v_suf,
+                           const void *k_pre, const void *v_pre, const int32_t *pre_len,
+                           const int32_t *suf_len, double *out, double *lse, double *probs, int nthreads)
+{
+    if (Np < 0 || C < 0 || S < 1 || Pp < 0 || Hq < 1 || Hkv < 1 || D < 1 || Hq % Hkv != 0)
+        return 1;
+    if (dtype < 0 || dtype > 2 || !out || !q || !k_suf || !v_suf || (Pp > 0 && (!k_pre || !v_pre)))
+        return 1;
+    const int64_t B = (int64_t)Np * C;
+    for (int n = 0; n < Np; ++n)
+        if (pre_len && (pre_len[n] < 0 || pre_len[n] > Pp))
+            return 1;
+    for (int64_t b = 0; b < B; ++b)
+        if (suf_len && (suf_len[b] < 0 || suf_len[b] > S))
+            return 1;
+    const int G = Hq / Hkv;
+    const int64_t W = (int64_t)Pp + S;
+    int failed = 0;
+#ifdef _OPENMP
+    if (nthreads > 0)
+        omp_set_num_threads(nthreads);
+#else
+    (void)nthreads;
+#endif
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t bk = 0; bk < B * Hkv; ++bk) {
+        const int64_t b = bk / Hkv;
+        const int k = (int)(bk % Hkv);
+        const int n = (int)(b / C);                 /* the candidate's instruction */
+        const int np = pre_len ? pre_len[n] : Pp;   /* its real prefix rows ...   */
+        const int64_t first = (int64_t)Pp - np;     /* ... start here (left padding before) */
+        const int len = suf_len ? suf_len[b] : S;
+        const int64_t T = (int64_t)np + len;
+
+        double *Kfull = (double *)malloc(sizeof(double) * (size_t)(T > 0 ? T : 1) * D);
+        double *Vfull = (double *)malloc(sizeof(double) * (size_t)(T > 0 ? T : 1) * D);
+        double *s = (double *)malloc(sizeof(double) * (size_t)(T > 0 ? T : 1));
+        if (!Kfull || !Vfull || !s) {
+#pragma omp atomic write
+            failed = 1;
+            free(Kfull); free(Vfull); free(s);
+            continue;
+        }
+        for (int64_t j = 0; j < np; ++j)
+            for (int d = 0; d < D; ++d) {
+                const int64_t src = ((((int64_t)n * Pp) + first + j) * Hkv + k) * D + d;
+                Kfull[j * D + d] = widen(k_pre, src, dtype);
+                Vfull[j * D + d] = widen(v_pre, src, dtype);
+            }
+        for (int64_t t = 0; t < len; ++t)
+            for (int d = 0; d < D; ++d) {
+                const int64_t src = ((b * S + t) * Hkv + k) * D + d;
+                Kfull[(np + t) * D + d] = widen(k_suf, src, dtype);
+                Vfull[(np + t) * D + d] = widen(v_suf, src, dtype);
+            }
+
+        for (int g = 0; g < G; ++g) {
+            const int h = k * G + g;
+            for (int i = 0; i < S; ++i) {
+                double *o = out + ((b * S + i) * Hq + h) * D;
+                double *pr = probs ? probs + ((b * Hq + h) * S + i) * W : NULL;
+                for (int d = 0; d < D; ++d)
+                    o[d] = 0.0;
+                if (pr)
+                    for (int64_t j = 0; j < W; ++j)
+                        pr[j] = 0.0;
+                if (i >= len) {
+                    if (lse)
+                        lse[(b * Hq + h) * S + i] = -INFINITY;
+                    continue;
+                }
+                const int64_t nvis = (int64_t)np + i + 1; /* real prefix rows, suffix rows 0..i */
+                const int64_t qoff = ((b * S + i) * Hq + h) * D;
+                double m = -INFINITY;
+                for (int64_t j = 0; j < nvis; ++j) {
+                    double acc = 0.0;
+                    for (int d = 0; d < D; ++d)
+                        acc += widen(q, qoff + d, dtype) * Kfull[j * D + d];
+                    s[j] = acc * scale;
+                    if (s[j] > m)
+                        m = s[j];
+                }
+                double denom = 0.0;
+                for (int64_t j = 0; j < nvis; ++j) {
+                    s[j] = exp(s[j] - m);
+                    denom += s[j];
+                }
+                for (int64_t j = 0; j < nvis; ++j) {
+                    const double p = s[j] / denom;
+                    if (pr)
+                        pr[j < np ? first + j : (int64_t)Pp + (j - np)] = p;
+                    for (int d = 0; d < D; ++d)
+                        o[d] += p * Vfull[j * D + d];
+                }
+                if (lse)
+                    lse[(b * Hq + h) * S + i] = m + log(denom);
+            }
+        }
+        free(Kfull); free(Vfull); free(s);
+    }
+    return failed ? 2 : 0;
+}

@@ -44,6 +44,9 @@ def _load():
         lib.pskv_oracle_attn.restype = ctypes.c_int
         lib.pskv_oracle_attn.argtypes = [ctypes.c_int] * 7 + [ctypes.c_double] + \
             [ctypes.c_void_p] * 9 + [ctypes.c_int]
+        lib.pskv_oracle_attn_multi.restype = ctypes.c_int
+        lib.pskv_oracle_attn_multi.argtypes = [ctypes.c_int] * 8 + [ctypes.c_double] + \
+            [ctypes.c_void_p] * 10 + [ctypes.c_int]
         lib.pskv_oracle_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -90,6 +93,48 @@ def attn(q, k_suf, v_suf, k_pre, v_pre, suf_len, scale: float, dtype: str,
                                   ptr(sl), ptr(out), ptr(lse), ptr(probs), int(nthreads))
     if rc != 0:
         raise RuntimeError(f"pskv_oracle_attn failed with code {rc}")
+    res = (out,)
+    if want_lse:
+        res += (lse,)
+    if want_probs:
+        res += (probs,)
+    return res[0] if len(res) == 1 else res
+
+
+def attn_multi(q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, scale: float, dtype: str,
+               want_lse: bool = False, want_probs: bool = False, nthreads: int = 0):
+    """Batched multi-instruction form (Sec. 4.3): k_pre, v_pre are [Np,Pp,Hkv,D], left-padded,
+    with pre_len [Np] real rows each; candidate b belongs to instruction b // (B // Np).
+    Returns out [B,S,Hq,D] float64 (+ lse [B,Hq,S], + probs [B,Hq,S,Pp+S])."""
+    B, S, Hq, D = q.shape
+    Hkv = k_suf.shape[2]
+    Np, Pp = k_pre.shape[0], k_pre.shape[1]
+    if Np == 0 or B % Np != 0:
+        raise ValueError("the number of candidates must be a multiple of the number of instructions")
+    C = B // Np
+    q = _check(q, (B, S, Hq, D), dtype, "q")
+    k_suf = _check(k_suf, (B, S, Hkv, D), dtype, "k_suf")
+    v_suf = _check(v_suf, (B, S, Hkv, D), dtype, "v_suf")
+    k_pre = _check(k_pre, (Np, Pp, Hkv, D), dtype, "k_pre")
+    v_pre = _check(v_pre, (Np, Pp, Hkv, D), dtype, "v_pre")
+    pl = None if pre_len is None else np.ascontiguousarray(pre_len, dtype=np.int32)
+    sl = None if suf_len is None else np.ascontiguousarray(suf_len, dtype=np.int32)
+    if pl is not None and pl.shape != (Np,):
+        raise ValueError("pre_len shape")
+    if sl is not None and sl.shape != (B,):
+        raise ValueError("suf_len shape")
+    out = np.empty((B, S, Hq, D), dtype=np.float64)
+    lse = np.empty((B, Hq, S), dtype=np.float64) if want_lse else None
+    probs = np.empty((B, Hq, S, Pp + S), dtype=np.float64) if want_probs else None
+
+    def ptr(a):
+        return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+    rc = _load().pskv_oracle_attn_multi(Np, C, S, Pp, Hq, Hkv, D, _DT[dtype], float(scale),
+                                        ptr(q), ptr(k_suf), ptr(v_suf), ptr(k_pre), ptr(v_pre),
+                                        ptr(pl), ptr(sl), ptr(out), ptr(lse), ptr(probs), int(nthreads))
+    if rc != 0:
+        raise RuntimeError(f"pskv_oracle_attn_multi failed with code {rc}")
     res = (out,)
     if want_lse:
         res += (lse,)
