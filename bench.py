@@ -25,16 +25,22 @@ PEAK_F64_TFLOPS = 78.6        # MI355X fp64 vector
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 
 
-def alg_counts(w, suf_len):
+def alg_counts(w, suf_len, pre_len=None):
     """Algorithmic work of one call: multiply-adds over visible keys only at 2 FLOP each, and
     the bytes that must cross HBM once (valid Q rows in, valid O rows out, valid suffix K/V
-    rows in, prefix K/V once)."""
+    rows in, every real prefix K/V row once).  pre_len: real prefix rows per instruction of
+    the multi-instruction form (None: one shared prefix of w.P rows)."""
     import numpy as np
     l = suf_len.astype(np.int64)
     e = 2 if w.dtype == "bf16" else 4
-    flops = int((w.Hq * 4 * w.D * (l * w.P + l * (l + 1) // 2)).sum())
-    exps = int((w.Hq * (l * w.P + l * (l + 1) // 2)).sum())
-    prefix_bytes = 2 * w.P * w.Hkv * w.D * e
+    if pre_len is None:
+        P, prefix_rows = w.P, w.P
+    else:
+        P = np.repeat(pre_len.astype(np.int64), w.C)      # the candidate's own prefix length
+        prefix_rows = int(pre_len.astype(np.int64).sum())
+    flops = int((w.Hq * 4 * w.D * (l * P + l * (l + 1) // 2)).sum())
+    exps = int((w.Hq * (l * P + l * (l + 1) // 2)).sum())
+    prefix_bytes = 2 * prefix_rows * w.Hkv * w.D * e
     bytes_ = int(l.sum()) * (2 * w.Hq + 2 * w.Hkv) * w.D * e + prefix_bytes
     return flops, bytes_, prefix_bytes, exps
 
@@ -69,6 +75,24 @@ def cpu_baseline(inp, budget_s=12.0):
     return {"value": done / t_total, "unit": "candidates/s", "cores": orc.threads(), "kind": "oracle",
             "sample": f"{done} candidates (the {w.B} of {w.name} taken in order, wrapping round; all heads), "
                       f"{t_total:.1f} s of oracle time"}
+
+
+def cpu_baseline_multi(inp, budget_s=12.0):
+    """The multi-instruction oracle timed on whole instructions of the same workload, in order."""
+    import numpy as np
+    from oracle import pskv_oracle as orc
+    w = inp.w
+    t_total, done, n = 0.0, 0, 0
+    while t_total < budget_s:
+        sub = inp.take_instructions(np.array([n % w.Np]))
+        t0 = time.perf_counter()
+        orc.attn_multi(sub.q, sub.k_suf, sub.v_suf, sub.k_pre, sub.v_pre, sub.pre_len, sub.suf_len, sub.scale, w.dtype)
+        t_total += time.perf_counter() - t0
+        done += w.C
+        n += 1
+    return {"value": done / t_total, "unit": "candidates/s", "cores": orc.threads(), "kind": "oracle",
+            "sample": f"{n} instructions with their {w.C} candidates each (those of {w.name} in order, wrapping "
+                      f"round; all heads), {t_total:.1f} s of oracle time"}
 
 
 def main():
@@ -108,16 +132,22 @@ def main():
         print(json.dumps({"copy_calibration": True, "launches": 10, "read_bytes_per_launch": 2 * n,
                           "written_bytes_per_launch": 2 * n}), flush=True)
         return
-    w = gen.WORKLOADS[args.workload]
-    inp = gen.make_inputs(w, pad="zero", workers=16)
-    flops, bytes_, prefix_bytes, exps = alg_counts(w, inp.suf_len)
+    multi = args.workload in gen.MULTI_WORKLOADS
+    if multi:
+        w = gen.MULTI_WORKLOADS[args.workload]
+        inp = gen.make_multi_inputs(w, pad="zero")
+        flops, bytes_, prefix_bytes, exps = alg_counts(w, inp.suf_len, inp.pre_len)
+    else:
+        w = gen.WORKLOADS[args.workload]
+        inp = gen.make_inputs(w, pad="zero", workers=16)
+        flops, bytes_, prefix_bytes, exps = alg_counts(w, inp.suf_len)
 
     # Rotating buffer sets so Q/K/V/O of consecutive calls do not sit in the 256 MB
     # last-level cache: each set is a full copy of the suffix-side tensors and output.
     e = 2 if w.dtype == "bf16" else 4
     set_bytes = (2 * w.B * w.S * w.Hq + 2 * w.B * w.S * w.Hkv) * w.D * e
     nsets = args.sets or int(max(2, min(8, (1 << 30) // max(1, set_bytes) + 1)))
-    base = pu.to_device(inp)
+    base = pu.to_device_multi(inp) if multi else pu.to_device(inp)
     sets = []
     for s in range(nsets):
         d = base if s == 0 else {k: (v.clone() if k in ("q", "k_suf", "v_suf") else v) for k, v in base.items()}
@@ -128,8 +158,13 @@ def main():
     stream = torch.cuda.current_stream().cuda_stream
 
     # arguments marshalled once per buffer set: the timed loop is one foreign call per step
-    prepared = [pk.PreparedCall(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], d["out"],
-                                impl=args.impl, scale=inp.scale, stream=stream) for d in sets]
+    if multi:
+        prepared = [pk.PreparedMultiCall(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["pre_len"],
+                                         d["suf_len"], d["out"], impl=args.impl, scale=inp.scale, stream=stream)
+                    for d in sets]
+    else:
+        prepared = [pk.PreparedCall(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], d["out"],
+                                    impl=args.impl, scale=inp.scale, stream=stream) for d in sets]
 
     def call(i):
         prepared[i]()
@@ -157,16 +192,24 @@ def main():
     # average duration of one launch (plus the idle gap between two launches, if any).
     kern_ms = ev_ms
     # For comparison, launches timed one at a time by the library's own event-bracketed helper.
-    per_set = [pk.pskv_attn_fwd_timed(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"],
-                                      d["suf_len"], d["out"], impl=args.impl, scale=inp.scale, iters=1,
-                                      stream=stream)
-               for _ in range(max(1, min(20, args.steps // nsets))) for d in sets]
-    isolated_ms = float(np.mean(per_set))
+    isolated_ms = None
+    if not multi:
+        per_set = [pk.pskv_attn_fwd_timed(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"],
+                                          d["suf_len"], d["out"], impl=args.impl, scale=inp.scale, iters=1,
+                                          stream=stream)
+                   for _ in range(max(1, min(20, args.steps // nsets))) for d in sets]
+        isolated_ms = float(np.mean(per_set))
 
     # quick self-check of the timed configuration on a few candidates (not timed)
-    cand = np.array([0, w.B // 2, w.B - 1])
-    sub = inp.take(cand)
-    ref = pu.oracle_out(sub)
+    if multi:
+        which = np.array([0, w.Np - 1])
+        sub = inp.take_instructions(which)
+        ref = pu.oracle_out_multi(sub)
+        cand = (which[:, None] * w.C + np.arange(w.C)[None, :]).reshape(-1)
+    else:
+        cand = np.array([0, w.B // 2, w.B - 1])
+        sub = inp.take(cand)
+        ref = pu.oracle_out(sub)
     got = pu.out_to_f64(sets[0]["out"][torch.from_numpy(cand).to("cuda:0")])
     chk = pu.compare(got, ref, sub.suf_len, w.dtype, "bench self-check")
 
@@ -204,7 +247,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "P": w.P, "S": w.S, "suffix_len": [w.len_lo, w.len_hi],
                    "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "impl": args.impl, "buffer_sets": nsets,
-                   "seed": w.seed},
+                   "seed": w.seed, **({"instructions": w.Np, "candidates_per_instruction": w.C,
+                                       "prefix_len": [w.pre_lo, w.pre_hi]} if multi else {})},
         "achieved_tflops": flops / (ms_per_step * 1e-3) / 1e12,
         "event_ms_per_step": ev_ms,
         "roofline": roof, "roofline_" + other["bound"]: other,
@@ -212,7 +256,7 @@ def main():
         "self_check": chk,
     }
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(inp)
+        line["cpu_baseline"] = cpu_baseline_multi(inp) if multi else cpu_baseline(inp)
     print(json.dumps(line), flush=True)
 
 

@@ -142,6 +142,48 @@ pskv_status pskv_attn_fwd_timed(const pskv_attn_params *p,
                                 void *workspace, size_t workspace_bytes,
                                 void *hip_stream, int iters, float *ms_per_call);
 
+/*
+ * Batched multi-instruction form (paper Sec. 4.3, suffix-centric alignment; App. F.1, position
+ * consistency under padding).  Np instructions are evaluated in one call: every instruction has
+ * its own prefix K/V, LEFT-padded to the common length base.P (its real rows are the last
+ * pre_len[n] ones; the padding rows are excluded from attention and may hold anything), and
+ * owns C = base.B / Np consecutive candidates: candidate b belongs to instruction b / C.
+ * All suffixes start at column 0 of the same dense [B,S,...] tensors, exactly as in the
+ * single-instruction call.  A candidate attends to the real prefix rows of its own instruction
+ * and causally to its own suffix rows; one prefix cache per instruction is read once and
+ * reused by that instruction's candidates, never expanded over them.
+ *
+ * base describes everything but the prefix batch: base.B = Np*C candidates, base.P = padded
+ * prefix length, base.kp_stride_p / kp_stride_h = strides inside one instruction's prefix.
+ */
+typedef struct {
+    pskv_attn_params base;
+    int32_t Np;          /* number of instructions, >= 1; base.B % Np == 0 */
+    int32_t reserved;    /* must be 0 */
+    int64_t kp_stride_n; /* elements between instructions in k_pre / v_pre; 0 = contiguous [Np,P,Hkv,D] */
+} pskv_multi_params;
+
+/* Host-only check of a multi-instruction params struct, same rules as pskv_attn_fwd_multi. */
+pskv_status pskv_attn_multi_validate(const pskv_multi_params *p);
+
+/*
+ * Forward pass of the multi-instruction form.  Arguments as for pskv_attn_fwd, except:
+ *
+ *   k_pre, v_pre [Np,P,Hkv,D]  device, read-only, one left-padded prefix per instruction
+ *   pre_len      [Np] int32    device, real prefix rows of each instruction, values in [0,P]
+ *                              (clamped on the device); NULL means every prefix has P real rows
+ *
+ * With Np == 1 and pre_len == NULL this is pskv_attn_fwd.  Same ownership, stream and error
+ * rules; no workspace is needed (workspace may be NULL).
+ */
+pskv_status pskv_attn_fwd_multi(const pskv_multi_params *p,
+                                const void *q, const void *k_suf, const void *v_suf,
+                                const void *k_pre, const void *v_pre,
+                                const int32_t *pre_len, const int32_t *suf_len,
+                                void *out, float *lse,
+                                void *workspace, size_t workspace_bytes,
+                                void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

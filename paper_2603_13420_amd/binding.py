@@ -18,7 +18,8 @@ PSKV_IMPL_AUTO, PSKV_IMPL_SIMPLE, PSKV_IMPL_MFMA = 0, 1, 2
 _IMPL = {"auto": PSKV_IMPL_AUTO, "simple": PSKV_IMPL_SIMPLE, "mfma": PSKV_IMPL_MFMA}
 
 EXPORTS = ["pskv_version", "pskv_status_str", "pskv_last_error", "pskv_attn_fwd_workspace_bytes",
-           "pskv_attn_validate", "pskv_attn_fwd", "pskv_attn_fwd_timed"]
+           "pskv_attn_validate", "pskv_attn_fwd", "pskv_attn_fwd_timed",
+           "pskv_attn_multi_validate", "pskv_attn_fwd_multi"]
 
 
 class pskv_attn_params(ctypes.Structure):
@@ -29,6 +30,11 @@ class pskv_attn_params(ctypes.Structure):
                    "ks_stride_b", "ks_stride_s", "ks_stride_h",
                    "kp_stride_p", "kp_stride_h",
                    "o_stride_b", "o_stride_s", "o_stride_h")]
+
+
+class pskv_multi_params(ctypes.Structure):
+    _fields_ = [("base", pskv_attn_params), ("Np", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("kp_stride_n", ctypes.c_int64)]
 
 
 class PskvError(RuntimeError):
@@ -64,6 +70,11 @@ def load():
     lib.pskv_attn_fwd.argtypes = fwd_args
     lib.pskv_attn_fwd_timed.restype = ctypes.c_int
     lib.pskv_attn_fwd_timed.argtypes = fwd_args + [ctypes.c_int, ctypes.POINTER(ctypes.c_float)]
+    PM = ctypes.POINTER(pskv_multi_params)
+    lib.pskv_attn_multi_validate.restype = ctypes.c_int
+    lib.pskv_attn_multi_validate.argtypes = [PM]
+    lib.pskv_attn_fwd_multi.restype = ctypes.c_int
+    lib.pskv_attn_fwd_multi.argtypes = [PM, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     _lib = lib
     return lib
 
@@ -220,3 +231,69 @@ def pskv_attn_fwd_timed(q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse=None, i
     if rc != PSKV_OK:
         _raise(rc)
     return float(ms.value)
+
+
+def make_multi_params(base: pskv_attn_params, Np: int, kp_stride_n: int = 0) -> pskv_multi_params:
+    p = pskv_multi_params()
+    p.base = base
+    p.Np = int(Np)
+    p.reserved = 0
+    p.kp_stride_n = int(kp_stride_n)
+    return p
+
+
+def pskv_attn_multi_validate(p: pskv_multi_params) -> int:
+    return int(load().pskv_attn_multi_validate(ctypes.byref(p)))
+
+
+def _multi_setup(q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, out, lse, impl, scale):
+    import torch
+    if k_pre is None or k_pre.dim() != 4 or tuple(v_pre.shape) != tuple(k_pre.shape) or v_pre.stride() != k_pre.stride():
+        raise ValueError("k_pre/v_pre must be [Np,P,Hkv,D] with shared strides")
+    Np = k_pre.shape[0]
+    if pre_len is not None and (pre_len.dtype != torch.int32 or tuple(pre_len.shape) != (Np,)
+                                or not pre_len.is_contiguous() or pre_len.device != q.device):
+        raise ValueError("pre_len must be a contiguous int32 [Np] tensor on the same device")
+    # one instruction's prefix has the [P,Hkv,D] form the single-prefix checks know
+    _check_inputs(q, k_suf, v_suf, k_pre[0], v_pre[0], suf_len, out, lse)
+    base = _params_from_tensors(q, k_suf, k_pre[0], out, impl, scale)
+    return make_multi_params(base, Np, k_pre.stride(0) if Np > 1 else 0)
+
+
+def pskv_attn_fwd_multi(q, k_suf, v_suf, k_pre, v_pre, pre_len=None, suf_len=None, out=None, lse=None,
+                        impl: str = "auto", scale: float = 0.0, stream: Optional[int] = None):
+    """Batched multi-instruction forward call: k_pre, v_pre are [Np,P,Hkv,D] (left-padded,
+    pre_len [Np] real rows each), candidate b belongs to instruction b // (B // Np)."""
+    import torch
+    if out is None:
+        out = torch.empty_like(q)
+    p = _multi_setup(q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, out, lse, impl, scale)
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    with torch.cuda.device(q.device):
+        rc = load().pskv_attn_fwd_multi(ctypes.byref(p), _ptr(q), _ptr(k_suf), _ptr(v_suf), _ptr(k_pre),
+                                        _ptr(v_pre), _ptr(pre_len), _ptr(suf_len), _ptr(out), _ptr(lse),
+                                        None, 0, ctypes.c_void_p(stream))
+    if rc != PSKV_OK:
+        _raise(rc)
+    return out
+
+
+class PreparedMultiCall:
+    """pskv_attn_fwd_multi with every argument marshalled once (see PreparedCall)."""
+
+    def __init__(self, q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, out, lse=None, impl: str = "auto",
+                 scale: float = 0.0, stream: Optional[int] = None):
+        import torch
+        self._keep = (q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, out, lse)
+        self._p = _multi_setup(q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, out, lse, impl, scale)
+        if stream is None:
+            stream = torch.cuda.current_stream(q.device).cuda_stream
+        self._args = (ctypes.byref(self._p), _ptr(q), _ptr(k_suf), _ptr(v_suf), _ptr(k_pre), _ptr(v_pre),
+                      _ptr(pre_len), _ptr(suf_len), _ptr(out), _ptr(lse), None, 0, ctypes.c_void_p(stream))
+        self._fn = load().pskv_attn_fwd_multi
+
+    def __call__(self):
+        rc = self._fn(*self._args)
+        if rc != PSKV_OK:
+            _raise(rc)

@@ -24,10 +24,16 @@ pskv_status fail(pskv_status s, const char *fmt, ...)
 constexpr size_t kSimpleMaxLds = 64 * 1024;
 
 // Fills `a` (without pointers) and `use_mfma` from p, applying every host-side rule.
-pskv_status resolve(const pskv_attn_params *p, pskv::Args &a, bool &use_mfma)
+// np, kp_stride_n: the instruction batch of the multi-instruction form (1, 0 for a single prefix).
+pskv_status resolve(const pskv_attn_params *p, int np, long long kp_stride_n, pskv::Args &a, bool &use_mfma)
 {
     if (!p)
         return fail(PSKV_ERR_INVALID_ARG, "params is NULL");
+    if (np < 1)
+        return fail(PSKV_ERR_INVALID_ARG, "Np=%d must be at least 1", np);
+    if (p->B >= 1 && p->B % np != 0)
+        return fail(PSKV_ERR_INVALID_ARG, "B=%d is not a multiple of Np=%d (every instruction owns B/Np consecutive candidates)",
+                    p->B, np);
     if (p->B < 1 || p->S < 1 || p->Hq < 1 || p->Hkv < 1 || p->D < 1 || p->P < 0)
         return fail(PSKV_ERR_INVALID_ARG, "sizes must satisfy B,S,Hq,Hkv,D >= 1 and P >= 0 (got B=%d S=%d P=%d Hq=%d Hkv=%d D=%d)",
                     p->B, p->S, p->P, p->Hq, p->Hkv, p->D);
@@ -52,6 +58,9 @@ pskv_status resolve(const pskv_attn_params *p, pskv::Args &a, bool &use_mfma)
 
     a.B = p->B; a.S = p->S; a.P = p->P; a.Hq = p->Hq; a.Hkv = p->Hkv; a.D = p->D;
     a.G = p->Hq / p->Hkv;
+    a.Np = np;
+    a.C = p->B / np;
+    a.plen = nullptr;
     a.div_g = pskv::make_fastdiv((unsigned)a.G);
     a.div_s = pskv::make_fastdiv((unsigned)a.S);
     a.scale = p->scale > 0.f ? p->scale : 1.0f / std::sqrt((float)p->D);
@@ -79,6 +88,17 @@ pskv_status resolve(const pskv_attn_params *p, pskv::Args &a, bool &use_mfma)
         *s.dst = s.given ? s.given : s.dflt;
     }
 
+    {
+        const long long one = (long long)p->P * a.kp_sp; // span of one instruction's prefix
+        if (kp_stride_n < 0)
+            return fail(PSKV_ERR_INVALID_ARG, "kp_stride_n=%lld is negative", kp_stride_n);
+        if (kp_stride_n != 0 && kp_stride_n % vec != 0)
+            return fail(PSKV_ERR_INVALID_ARG, "kp_stride_n=%lld is not a multiple of %d elements (16 bytes)", kp_stride_n, vec);
+        if (kp_stride_n != 0 && np > 1 && kp_stride_n < one)
+            return fail(PSKV_ERR_INVALID_ARG, "kp_stride_n=%lld is smaller than one prefix (%lld elements)", kp_stride_n, one);
+        a.kp_sn = kp_stride_n ? kp_stride_n : one;
+    }
+
     const bool mfma_ok = pskv::mfma_supported(a, p->dtype);
     if (p->impl == PSKV_IMPL_MFMA && !mfma_ok)
         return fail(PSKV_ERR_UNSUPPORTED, "the MFMA path needs dtype bf16 and D == 128 (got dtype=%d D=%d S=%d)",
@@ -91,6 +111,40 @@ pskv_status resolve(const pskv_attn_params *p, pskv::Args &a, bool &use_mfma)
 }
 
 bool misaligned(const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) != 0; }
+
+// Everything the two forward entry points share: checks, then one launch on the caller's stream.
+pskv_status launch(const pskv_attn_params *p, int np, long long kp_stride_n, const void *q, const void *k_suf,
+                   const void *v_suf, const void *k_pre, const void *v_pre, const int32_t *pre_len,
+                   const int32_t *suf_len, void *out, float *lse, void *hip_stream)
+{
+    pskv::Args a{};
+    bool use_mfma = false;
+    pskv_status s = resolve(p, np, kp_stride_n, a, use_mfma);
+    if (s != PSKV_OK)
+        return s;
+    if (!q || !k_suf || !v_suf || !out)
+        return fail(PSKV_ERR_INVALID_ARG, "q, k_suf, v_suf and out must not be NULL");
+    if (a.P > 0 && (!k_pre || !v_pre))
+        return fail(PSKV_ERR_INVALID_ARG, "k_pre and v_pre must not be NULL when P > 0");
+    const void *ptrs[] = {q, k_suf, v_suf, k_pre, v_pre, out};
+    for (const void *ptr : ptrs)
+        if (misaligned(ptr))
+            return fail(PSKV_ERR_INVALID_ARG, "data pointer %p is not 16-byte aligned", ptr);
+    if ((reinterpret_cast<uintptr_t>(suf_len) & 3u) || (reinterpret_cast<uintptr_t>(lse) & 3u) ||
+        (reinterpret_cast<uintptr_t>(pre_len) & 3u))
+        return fail(PSKV_ERR_INVALID_ARG, "suf_len, pre_len and lse must be 4-byte aligned");
+    if (out == q || out == k_suf || out == v_suf || out == k_pre || out == v_pre)
+        return fail(PSKV_ERR_INVALID_ARG, "out must not alias an input");
+
+    a.q = q; a.ks = k_suf; a.vs = v_suf; a.kp = k_pre; a.vp = v_pre;
+    a.len = suf_len; a.plen = pre_len; a.out = out; a.lse = lse;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = use_mfma ? pskv::launch_mfma(a, stream) : pskv::launch_simple(a, p->dtype, stream);
+    if (e != hipSuccess)
+        return fail(PSKV_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+    g_err[0] = '\0';
+    return PSKV_OK;
+}
 
 } // namespace
 
@@ -116,7 +170,7 @@ size_t pskv_attn_fwd_workspace_bytes(const pskv_attn_params *p)
 {
     pskv::Args a{};
     bool use_mfma = false;
-    if (resolve(p, a, use_mfma) != PSKV_OK)
+    if (resolve(p, 1, 0, a, use_mfma) != PSKV_OK)
         return (size_t)-1;
     return 0; // every path is fully fused
 }
@@ -125,7 +179,7 @@ pskv_status pskv_attn_validate(const pskv_attn_params *p)
 {
     pskv::Args a{};
     bool use_mfma = false;
-    pskv_status s = resolve(p, a, use_mfma);
+    pskv_status s = resolve(p, 1, 0, a, use_mfma);
     if (s == PSKV_OK)
         g_err[0] = '\0';
     return s;
@@ -138,32 +192,36 @@ pskv_status pskv_attn_fwd(const pskv_attn_params *p, const void *q, const void *
 {
     (void)workspace;
     (void)workspace_bytes; // no path needs scratch
+    return launch(p, 1, 0, q, k_suf, v_suf, k_pre, v_pre, nullptr, suf_len, out, lse, hip_stream);
+}
+
+pskv_status pskv_attn_multi_validate(const pskv_multi_params *p)
+{
+    if (!p)
+        return fail(PSKV_ERR_INVALID_ARG, "params is NULL");
+    if (p->reserved != 0)
+        return fail(PSKV_ERR_INVALID_ARG, "reserved field must be 0");
     pskv::Args a{};
     bool use_mfma = false;
-    pskv_status s = resolve(p, a, use_mfma);
-    if (s != PSKV_OK)
-        return s;
-    if (!q || !k_suf || !v_suf || !out)
-        return fail(PSKV_ERR_INVALID_ARG, "q, k_suf, v_suf and out must not be NULL");
-    if (a.P > 0 && (!k_pre || !v_pre))
-        return fail(PSKV_ERR_INVALID_ARG, "k_pre and v_pre must not be NULL when P > 0");
-    const void *ptrs[] = {q, k_suf, v_suf, k_pre, v_pre, out};
-    for (const void *ptr : ptrs)
-        if (misaligned(ptr))
-            return fail(PSKV_ERR_INVALID_ARG, "data pointer %p is not 16-byte aligned", ptr);
-    if ((reinterpret_cast<uintptr_t>(suf_len) & 3u) || (reinterpret_cast<uintptr_t>(lse) & 3u))
-        return fail(PSKV_ERR_INVALID_ARG, "suf_len and lse must be 4-byte aligned");
-    if (out == q || out == k_suf || out == v_suf || out == k_pre || out == v_pre)
-        return fail(PSKV_ERR_INVALID_ARG, "out must not alias an input");
+    pskv_status s = resolve(&p->base, p->Np, p->kp_stride_n, a, use_mfma);
+    if (s == PSKV_OK)
+        g_err[0] = '\0';
+    return s;
+}
 
-    a.q = q; a.ks = k_suf; a.vs = v_suf; a.kp = k_pre; a.vp = v_pre;
-    a.len = suf_len; a.out = out; a.lse = lse;
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    hipError_t e = use_mfma ? pskv::launch_mfma(a, stream) : pskv::launch_simple(a, p->dtype, stream);
-    if (e != hipSuccess)
-        return fail(PSKV_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
-    g_err[0] = '\0';
-    return PSKV_OK;
+pskv_status pskv_attn_fwd_multi(const pskv_multi_params *p, const void *q, const void *k_suf,
+                                const void *v_suf, const void *k_pre, const void *v_pre,
+                                const int32_t *pre_len, const int32_t *suf_len, void *out, float *lse,
+                                void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    (void)workspace;
+    (void)workspace_bytes; // no path needs scratch
+    if (!p)
+        return fail(PSKV_ERR_INVALID_ARG, "params is NULL");
+    if (p->reserved != 0)
+        return fail(PSKV_ERR_INVALID_ARG, "reserved field must be 0");
+    return launch(&p->base, p->Np, p->kp_stride_n, q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, out, lse,
+                  hip_stream);
 }
 
 pskv_status pskv_attn_fwd_timed(const pskv_attn_params *p, const void *q, const void *k_suf,

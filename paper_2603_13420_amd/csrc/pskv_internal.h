@@ -26,6 +26,12 @@ inline FastDiv make_fastdiv(unsigned d)
 
 struct Args {
     int B, S, P, Hq, Hkv, D, G;
+    // Batched multi-instruction form (Sec. 4.3): Np instructions with C = B / Np consecutive
+    // candidates each; the prefix tensors are [Np, P, Hkv, D], every prefix LEFT-padded to P rows
+    // with plen[n] real rows at the end.  Np == 1, plen == nullptr is the single shared prefix.
+    int Np, C;
+    const int *plen; // may be null: every prefix has P real rows
+    long long kp_sn; // elements from one instruction's prefix to the next
     FastDiv div_g, div_s; // division by G and by S
     float scale;
     const void *q, *ks, *vs, *kp, *vp;

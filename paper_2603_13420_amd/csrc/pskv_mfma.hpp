@@ -143,7 +143,12 @@ __device__ inline void softmax_tile(const floatx16 &s, RowState &st, float c, bf
 // Shared per-lane context
 // ------------------------------------------------------------------------------------------
 struct Ctx {
-    int lane, h, c32, head, Mtot;
+    int lane, h, c32, Mtot; // Mtot: stacked rows of one (instruction, KV head) pair = C*S*G
+    // the (instruction, KV head) pair being worked on ("virtual head")
+    int head;   // KV head
+    int cand0;  // first candidate of the instruction
+    int P;      // real prefix rows of the instruction
+    const unsigned short *kpg, *vpg; // first real prefix row of this instruction and KV head
     float c;          // softmax scale in log2 units
     lds_u8 *k_lane;   // K images + lane*16
     lds_u8 *v_lane;   // V images + lane*8
@@ -152,6 +157,28 @@ struct Ctx {
     int sv_chunk_lo;  // ... and its 16-byte chunk (+ 4*(fragment >> 1))
     const unsigned short *ksg, *vsg; // suffix K/V of this KV head
 };
+
+// Points the context at virtual head vh = instruction * Hkv + KV head: the instruction's real
+// prefix rows are the last plen[instruction] of its P padded rows (App. F.1: the prefix is
+// left-padded), so its prefix simply starts that much later and is that much shorter.
+__device__ inline void set_vhead(const Args &a, Ctx &X, int vh)
+{
+    typedef const __attribute__((address_space(4))) int *const_int_ptr;
+    const int n = vh / a.Hkv;
+    X.head = vh - n * a.Hkv;
+    X.cand0 = n * a.C;
+    int pl = a.P;
+    if (a.plen) {
+        pl = ((const_int_ptr)(unsigned long long)a.plen)[__builtin_amdgcn_readfirstlane(n)];
+        pl = pl < 0 ? 0 : (pl > a.P ? a.P : pl);
+    }
+    X.P = pl;
+    const long long off = (long long)n * a.kp_sn + (long long)(a.P - pl) * a.kp_sp + (long long)X.head * a.kp_sh;
+    X.kpg = reinterpret_cast<const unsigned short *>(a.kp) + off;
+    X.vpg = reinterpret_cast<const unsigned short *>(a.vp) + off;
+    X.ksg = reinterpret_cast<const unsigned short *>(a.ks) + (long long)X.head * a.ks_sh;
+    X.vsg = reinterpret_cast<const unsigned short *>(a.vs) + (long long)X.head * a.ks_sh;
+}
 
 // Row bookkeeping of one lane for one 32-row block.
 struct Row {
@@ -174,21 +201,22 @@ __device__ inline int len_uniform(const Args &a, int b)
     return clamp_len(a, ((const_int_ptr)(unsigned long long)a.len)[__builtin_amdgcn_readfirstlane(b)]);
 }
 
-__device__ inline Row decode_row(const Args &a, const Ctx &X, int blk, int head)
+__device__ inline Row decode_row(const Args &a, const Ctx &X, int blk, int head, int cand0)
 {
     Row x;
     const int r = blk * kBlockRows + X.c32;
     x.rin = r < X.Mtot;
     const unsigned rr = x.rin ? r : X.Mtot - 1;
     const unsigned tok = fdiv(rr, a.div_g), gq = rr - tok * a.G;
-    x.rb = fdiv(tok, a.div_s);
-    x.ri = tok - x.rb * a.S;
+    const unsigned bl = fdiv(tok, a.div_s); // candidate within the instruction
+    x.rb = cand0 + bl;
+    x.ri = tok - bl * a.S;
     x.rh = head * a.G + gq;
     x.rlen = a.len ? a.len[x.rb] : a.S;
     return x;
 }
 
-__device__ inline Row decode_row(const Args &a, const Ctx &X, int blk) { return decode_row(a, X, blk, X.head); }
+__device__ inline Row decode_row(const Args &a, const Ctx &X, int blk) { return decode_row(a, X, blk, X.head, X.cand0); }
 
 // Q fragments of a block: lane (row c32, half h) holds d = 16*ks + 8*h ..+7 for ks = 0..7.
 // Padded rows are loaded as they are: a row's values only ever reach its own column of S^T
@@ -279,8 +307,8 @@ __device__ inline void store_block(const Args &a, const Ctx &X, int r0, const Ro
         dst_ok[u] = r < X.Mtot;
         const unsigned rr = dst_ok[u] ? r : X.Mtot - 1;
         const unsigned tok = fdiv(rr, a.div_g), gq = rr - tok * a.G;
-        const unsigned b = fdiv(tok, a.div_s), i = tok - b * a.S;
-        dst[u] = reinterpret_cast<unsigned short *>(a.out) + (long long)b * a.o_sb + (long long)i * a.o_ss +
+        const unsigned bl = fdiv(tok, a.div_s), i = tok - bl * a.S;
+        dst[u] = reinterpret_cast<unsigned short *>(a.out) + (long long)(X.cand0 + bl) * a.o_sb + (long long)i * a.o_ss +
                  (long long)(X.head * a.G + gq) * a.o_sh + 8 * (X.lane & 7);
     }
 #pragma unroll
@@ -349,21 +377,20 @@ __device__ inline TileSlot make_tile_slot(int tid)
 
 // This thread's K and V chunks of prefix tile kt (rows clamped into the prefix: what lies past
 // it is zeroed when the chunks are written, see write_tile_chunks).
-__device__ inline void load_tile_chunks(const Args &a, const unsigned short *kpg, const unsigned short *vpg,
-                                        const TileSlot &t, int kt, uintx4 &kv, uintx4 &vv)
+__device__ inline void load_tile_chunks(const Args &a, const Ctx &X, const TileSlot &t, int kt, uintx4 &kv, uintx4 &vv)
 {
-    const int last = a.P > 0 ? a.P - 1 : 0;
+    const int last = X.P > 0 ? X.P - 1 : 0;
     const int kkey = kt * kTileKeys + t.k_row, vkey = kt * kTileKeys + t.v_row;
-    kv = ld_global16(kpg + (long long)(kkey < a.P ? kkey : last) * a.kp_sp + t.k_chunk * 8);
-    vv = ld_global16(vpg + (long long)(vkey < a.P ? vkey : last) * a.kp_sp + t.v_chunk * 8);
+    kv = ld_global16(X.kpg + (long long)(kkey < X.P ? kkey : last) * a.kp_sp + t.k_chunk * 8);
+    vv = ld_global16(X.vpg + (long long)(vkey < X.P ? vkey : last) * a.kp_sp + t.v_chunk * 8);
 }
 
-__device__ inline void write_tile_chunks(const Args &a, const TileSlot &t, int kt, lds_u8 *kimg, lds_u8 *vimg, int tid,
+__device__ inline void write_tile_chunks(const Ctx &X, const TileSlot &t, int kt, lds_u8 *kimg, lds_u8 *vimg, int tid,
                                          const uintx4 &kv, const uintx4 &vv)
 {
     const int kkey = kt * kTileKeys + t.k_row, vkey = kt * kTileKeys + t.v_row;
-    *(lds_u128 *)(kimg + tid * 16) = kkey < a.P ? kv : uintx4{0, 0, 0, 0};
-    *(lds_u128 *)(vimg + tid * 16) = vkey < a.P ? vv : uintx4{0, 0, 0, 0};
+    *(lds_u128 *)(kimg + tid * 16) = kkey < X.P ? kv : uintx4{0, 0, 0, 0};
+    *(lds_u128 *)(vimg + tid * 16) = vkey < X.P ? vv : uintx4{0, 0, 0, 0};
 }
 
 // Classic online-softmax step over one prefix tile whose images are in LDS (k_lane and v_lane
@@ -404,11 +431,12 @@ __device__ inline void suffix_classic(const Args &a, const Ctx &X, int r0, const
 {
     const int last_row = r0 + kBlockRows - 1 < X.Mtot ? r0 + kBlockRows - 1 : X.Mtot - 1;
     const int tok_first = fdiv(r0, a.div_g), tok_last = fdiv(last_row, a.div_g);
-    const int b_last = fdiv(tok_last, a.div_s);
-    for (int b = fdiv(tok_first, a.div_s); b <= b_last; ++b) {
+    const int bl_last = fdiv(tok_last, a.div_s);
+    for (int bl = fdiv(tok_first, a.div_s); bl <= bl_last; ++bl) { // candidates within the instruction
+        const int b = X.cand0 + bl;
         const int len = len_uniform(a, b);
-        const int i_lo = tok_first - b * a.S > 0 ? tok_first - b * a.S : 0;
-        const int i_hi = tok_last - b * a.S < a.S - 1 ? tok_last - b * a.S : a.S - 1;
+        const int i_lo = tok_first - bl * a.S > 0 ? tok_first - bl * a.S : 0;
+        const int i_hi = tok_last - bl * a.S < a.S - 1 ? tok_last - bl * a.S : a.S - 1;
         const int kmax = i_hi < len - 1 ? i_hi : len - 1; // last suffix key any row of this block sees
         if (i_lo >= len)
             continue;

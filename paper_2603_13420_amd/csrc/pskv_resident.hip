@@ -24,40 +24,37 @@ namespace {
 
 constexpr int kMaxTiles = 8; // resident prefix: at most 256 keys
 
-// Copies the prefix K/V of one head into the fragment-major LDS images (whole workgroup of 512
-// threads).  All global loads are issued before the first LDS write, so their latencies overlap.
-__device__ inline void stage_prefix(const Args &a, int head, int ntiles, lds_u8 *kimg, lds_u8 *vimg, int tid)
+// Copies the prefix K/V of the current virtual head into the fragment-major LDS images (whole
+// workgroup of 512 threads).  All global loads are issued before the first LDS write, so their
+// latencies overlap.
+__device__ inline void stage_prefix(const Args &a, const Ctx &X, int ntiles, lds_u8 *kimg, lds_u8 *vimg, int tid)
 {
-    const unsigned short *kpg = reinterpret_cast<const unsigned short *>(a.kp) + (long long)head * a.kp_sh;
-    const unsigned short *vpg = reinterpret_cast<const unsigned short *>(a.vp) + (long long)head * a.kp_sh;
     const TileSlot t = make_tile_slot(tid);
     uintx4 kv[kMaxTiles], vv[kMaxTiles];
 #pragma unroll
     for (int kt = 0; kt < kMaxTiles; ++kt)
         if (kt < ntiles)
-            load_tile_chunks(a, kpg, vpg, t, kt, kv[kt], vv[kt]);
+            load_tile_chunks(a, X, t, kt, kv[kt], vv[kt]);
 #pragma unroll
     for (int kt = 0; kt < kMaxTiles; ++kt)
         if (kt < ntiles)
-            write_tile_chunks(a, t, kt, kimg + kt * kTileBytes, vimg + kt * kTileBytes, tid, kv[kt], vv[kt]);
+            write_tile_chunks(X, t, kt, kimg + kt * kTileBytes, vimg + kt * kTileBytes, tid, kv[kt], vv[kt]);
 }
 
-__device__ inline Ctx make_ctx(const Args &a, lds_u8 *smem, int ntiles, int tid, int head)
+// max_tiles: tiles of the padded prefix length; it fixes the LDS layout for every instruction.
+__device__ inline Ctx make_ctx(const Args &a, lds_u8 *smem, int max_tiles, int tid)
 {
     Ctx X;
     X.lane = tid & 63;
     X.h = X.lane >> 5;
     X.c32 = X.lane & 31;
-    X.head = head;
-    X.Mtot = a.B * a.S * a.G;
+    X.Mtot = a.C * a.S * a.G;
     X.c = a.scale * kLog2e;
     X.k_lane = smem + X.lane * 16;
-    X.v_lane = smem + ntiles * kTileBytes + X.lane * 8;
-    X.scr = smem + 2 * ntiles * kTileBytes + __builtin_amdgcn_readfirstlane(tid >> 6) * kScrBytes;
+    X.v_lane = smem + max_tiles * kTileBytes + X.lane * 8;
+    X.scr = smem + 2 * max_tiles * kTileBytes + __builtin_amdgcn_readfirstlane(tid >> 6) * kScrBytes;
     X.sv_row_lo = 4 * ((X.c32 >> 4) & 1) + ((X.c32 >> 1) & 3);
     X.sv_chunk_lo = 2 * ((X.c32 >> 3) & 1) + (X.c32 & 1);
-    X.ksg = reinterpret_cast<const unsigned short *>(a.ks) + (long long)head * a.ks_sh;
-    X.vsg = reinterpret_cast<const unsigned short *>(a.vs) + (long long)head * a.ks_sh;
     return X;
 }
 
@@ -86,26 +83,36 @@ __device__ __attribute__((always_inline)) void general_block(const Args &a, cons
         for (int e = 0; e < 16; ++e)
             st.o[dt][e] = 0.f;
 
-    for (int kt = 0; kt < ntiles; ++kt) // prefix part: every row sees every prefix key
-        prefix_tile_classic(X, X.k_lane + kt * kTileBytes, X.v_lane + kt * kTileBytes, a.P - kt * kTileKeys, q, st);
+    for (int kt = 0; kt < ntiles; ++kt) // prefix part: every row sees every real prefix key
+        prefix_tile_classic(X, X.k_lane + kt * kTileBytes, X.v_lane + kt * kTileBytes, X.P - kt * kTileKeys, q, st);
     suffix_classic(a, X, r0, row, q, st);
     store_block(a, X, r0, row, rvalid, st.m, st.l, st.o);
 }
 
+// Work distribution shared by both kernels.  A "virtual head" is one (instruction, KV head)
+// pair; there are VH = Np*Hkv of them, each with its own prefix and its own C*S*G stacked
+// rows.  The grid is per_vh * vh_slots workgroups: workgroup w serves virtual heads
+// w % vh_slots, + vh_slots, ... (consecutive workgroup ids, one per XCD in turn, take
+// consecutive KV heads) and, within each, the row blocks of slice w / vh_slots out of per_vh.
 __global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
-void resident_general_kernel(Args a, int wgs_per_head, int ntiles)
+void resident_general_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
 {
     extern __shared__ __align__(16) unsigned char smem_generic[];
     lds_u8 *smem = (lds_u8 *)smem_generic;
     const int tid = threadIdx.x;
-    const int head = blockIdx.x % a.Hkv; // consecutive workgroup ids (one per XCD in turn) take consecutive heads
-    const Ctx X = make_ctx(a, smem, ntiles, tid, head);
-    stage_prefix(a, head, ntiles, smem, smem + ntiles * kTileBytes, tid);
-    __syncthreads();
+    Ctx X = make_ctx(a, smem, max_tiles, tid);
     const int nblocks = (X.Mtot + kBlockRows - 1) / kBlockRows;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    for (int blk = (blockIdx.x / a.Hkv) * kNW + wave; blk < nblocks; blk += wgs_per_head * kNW)
-        general_block(a, X, ntiles, blk);
+    const int VH = a.Np * a.Hkv;
+    for (int vh = blockIdx.x % vh_slots; vh < VH; vh += vh_slots) {
+        set_vhead(a, X, vh);
+        const int ntiles = (X.P + kTileKeys - 1) / kTileKeys;
+        __syncthreads(); // every wavefront is done with the images of the virtual head before
+        stage_prefix(a, X, ntiles, smem, smem + max_tiles * kTileBytes, tid);
+        __syncthreads();
+        for (int blk = (blockIdx.x / vh_slots) * kNW + wave; blk < nblocks; blk += per_vh * kNW)
+            general_block(a, X, ntiles, blk);
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -121,20 +128,19 @@ void resident_general_kernel(Args a, int wgs_per_head, int ntiles)
 // registers).
 // ------------------------------------------------------------------------------------------
 __global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
-void resident_pipelined_kernel(Args a, int wgs_per_head, int ntiles)
+void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
 {
     extern __shared__ __align__(16) unsigned char smem_generic[];
     lds_u8 *smem = (lds_u8 *)smem_generic;
     const int tid = threadIdx.x;
-    const int head = blockIdx.x % a.Hkv; // consecutive workgroup ids (one per XCD in turn) take consecutive heads
-    const Ctx X = make_ctx(a, smem, ntiles, tid, head);
+    Ctx X = make_ctx(a, smem, max_tiles, tid);
     const int nblocks = (X.Mtot + kBlockRows - 1) / kBlockRows;
-    const int blk_stride = wgs_per_head * kNW;
-    const int T = ntiles;
+    const int blk_stride = per_vh * kNW;
+    const int VH = a.Np * a.Hkv;
     auto kimg = [&](int t) { return X.k_lane + t * kTileBytes; };
     auto vimg = [&](int t) { return X.v_lane + t * kTileBytes; };
 
-    // First key a block's rows can see and last suffix position its rows have, from its index:
+    // Candidate (within the instruction) and first suffix position of a block, from its index:
     // block blk covers rows [32*blk, 32*blk+31] of candidate 32*blk / (S*G).
     // A block whose first row is already past its candidate's length holds nothing but padding.
     auto block_cand = [&](int blk) { return (int)fdiv(fdiv(blk * kBlockRows, a.div_g), a.div_s); };
@@ -142,23 +148,34 @@ void resident_pipelined_kernel(Args a, int wgs_per_head, int ntiles)
     // Advance to the next block of this wavefront that has a valid row; blocks of pure padding
     // on the way are stored as zeros here and now.
     auto skip_padding = [&](int blk) {
-        while (blk < nblocks && block_i_lo(blk) >= len_uniform(a, block_cand(blk))) {
+        while (blk < nblocks && block_i_lo(blk) >= len_uniform(a, X.cand0 + block_cand(blk))) {
             store_zero_block(a, X, decode_row(a, X, blk));
             blk += blk_stride;
         }
         return blk;
     };
 
+    for (int vh = blockIdx.x % vh_slots; vh < VH; vh += vh_slots) {
+    set_vhead(a, X, vh);
+    const int T = (X.P + kTileKeys - 1) / kTileKeys;
+
     // first block of this wavefront: request its row decode and Q before the prefix copy
-    const int first_blk = (blockIdx.x / a.Hkv) * kNW + __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int first_blk = (blockIdx.x / vh_slots) * kNW + __builtin_amdgcn_readfirstlane(tid >> 6);
     bool any_bad = false;
     int blk = skip_padding(first_blk);
     Row nxt = decode_row(a, X, blk < nblocks ? blk : nblocks - 1);
     uintx4 q[8]; // this block's Q fragments until their last use, then the next block's
     load_q(a, X, nxt, q);
 
-    stage_prefix(a, head, ntiles, smem, smem + ntiles * kTileBytes, tid);
+    __syncthreads(); // every wavefront is done with the images of the virtual head before
+    stage_prefix(a, X, T, smem, smem + max_tiles * kTileBytes, tid);
     __syncthreads();
+
+    if (T < 3) { // this instruction's prefix is too short for the pipeline: general path
+        for (int b2 = first_blk; b2 < nblocks; b2 += blk_stride)
+            general_block(a, X, T, b2);
+        continue;
+    }
 
     while (blk < nblocks) {
         const int r0 = blk * kBlockRows;
@@ -168,11 +185,11 @@ void resident_pipelined_kernel(Args a, int wgs_per_head, int ntiles)
         // the block's suffix step: candidate sb, keys 0..skmax
         const int sb = block_cand(blk);
         const int i_hi = (int)fdiv(r0 + kBlockRows - 1, a.div_g) - sb * a.S;
-        const int len = len_uniform(a, sb);
+        const int len = len_uniform(a, X.cand0 + sb);
         const int skmax = i_hi < len - 1 ? i_hi : len - 1;
         // Loads are retired in issue order, so what is needed last is requested first.
         uintx4 skf[8], svf[2][4];
-        load_suffix_k(a, X, sb, 0, skmax, skf);
+        load_suffix_k(a, X, X.cand0 + sb, 0, skmax, skf);
 
         // ---- first prefix tile: scores, reference maximum ----
         floatx16 sA, sB; // raw scores of the current and of the next tile, roles alternating
@@ -216,14 +233,14 @@ void resident_pipelined_kernel(Args a, int wgs_per_head, int ntiles)
             pB[0] = pA[0];
             pB[1] = pA[1];
         }
-        if (a.P & (kTileKeys - 1)) { // ragged last prefix tile: keys past the prefix are not visible
-            const int nv = a.P - (T - 1) * kTileKeys - 4 * X.h;
+        if (X.P & (kTileKeys - 1)) { // ragged last prefix tile: keys past the prefix are not visible
+            const int nv = X.P - (T - 1) * kTileKeys - 4 * X.h;
 #pragma unroll
             for (int e = 0; e < 16; ++e)
                 if (8 * (e >> 2) + (e & 3) >= nv)
                     sA[e] = -INFINITY;
         }
-        load_suffix_v(a, X, sb, 0, skmax, svf); // one step ahead of its use
+        load_suffix_v(a, X, X.cand0 + sb, 0, skmax, svf); // one step ahead of its use
         // ---- last prefix tile: the "next scores" are the suffix scores, from the K registers ----
         pipe_tile<true, true, true, false, false, false, true>(kimg(0), skf, vimg(T - 2), kimg(0), vimg(T - 1), pre, q, sA,
                                                                sB, X.c, m, 0, l, pB, pA, o);
@@ -251,7 +268,8 @@ void resident_pipelined_kernel(Args a, int wgs_per_head, int ntiles)
     // stored is replaced by the general path's result.
     if (any_bad)
         for (int b2 = first_blk; b2 < nblocks; b2 += blk_stride)
-            general_block(a, X, ntiles, b2);
+            general_block(a, X, T, b2);
+    } // virtual heads
 }
 
 } // namespace
@@ -280,22 +298,27 @@ hipError_t launch_resident(const Args &a, hipStream_t stream)
             return e;
         num_cu = n > 0 ? n : 256;
     }
-    const int ntiles = (a.P + kTileKeys - 1) / kTileKeys;
-    const long long rows = (long long)a.B * a.S * a.G;
+    const int max_tiles = (a.P + kTileKeys - 1) / kTileKeys;
+    const long long rows = (long long)a.C * a.S * a.G; // stacked rows of one virtual head
     const long long nblocks = (rows + kBlockRows - 1) / kBlockRows;
-    // one workgroup per compute unit, split evenly over the KV heads; never more workgroups
-    // per head than there are groups of 8 row blocks
-    long long per_head = num_cu / a.Hkv > 0 ? num_cu / a.Hkv : 1;
+    const long long VH = (long long)a.Np * a.Hkv;
+    // One workgroup per compute unit.  With fewer virtual heads than compute units the
+    // workgroups are split evenly over them (never more per virtual head than there are
+    // groups of 8 row blocks); with more, every workgroup takes several in turn.
+    const long long vh_slots = VH < num_cu ? VH : num_cu;
+    long long per_vh = num_cu / vh_slots;
     const long long useful = (nblocks + kNW - 1) / kNW;
-    if (per_head > useful)
-        per_head = useful;
-    const unsigned grid = (unsigned)(per_head * a.Hkv);
-    const size_t lds = (size_t)2 * ntiles * kTileBytes + kNW * kScrBytes;
-    const bool pipelined = ((long long)a.S * a.G) % kBlockRows == 0 && a.S <= kTileKeys && ntiles >= 3;
+    if (per_vh > useful)
+        per_vh = useful;
+    const unsigned grid = (unsigned)(per_vh * vh_slots);
+    const size_t lds = (size_t)2 * max_tiles * kTileBytes + kNW * kScrBytes;
+    const bool pipelined = ((long long)a.S * a.G) % kBlockRows == 0 && a.S <= kTileKeys && max_tiles >= 3;
     if (pipelined)
-        hipLaunchKernelGGL(resident_pipelined_kernel, dim3(grid), dim3(kNW * 64), lds, stream, a, (int)per_head, ntiles);
+        hipLaunchKernelGGL(resident_pipelined_kernel, dim3(grid), dim3(kNW * 64), lds, stream, a, (int)per_vh,
+                           (int)vh_slots, max_tiles);
     else
-        hipLaunchKernelGGL(resident_general_kernel, dim3(grid), dim3(kNW * 64), lds, stream, a, (int)per_head, ntiles);
+        hipLaunchKernelGGL(resident_general_kernel, dim3(grid), dim3(kNW * 64), lds, stream, a, (int)per_vh,
+                           (int)vh_slots, max_tiles);
     return hipGetLastError();
 }
 

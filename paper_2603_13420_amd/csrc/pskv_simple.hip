@@ -1,8 +1,8 @@
 // Simple path of batched candidate-suffix attention: one wavefront per query row (b,i,h).
 //
-// It follows Eq. 2 of the paper literally over the visible keys - all P rows of the single
-// shared prefix K/V (read in place, never expanded over candidates) and rows 0..i of the
-// candidate's own suffix K/V - in three sweeps: scores (lane per key), max/exp/sum, and the
+// It follows Eq. 2 of the paper literally over the visible keys - the real rows of the prefix
+// K/V of the candidate's instruction (read in place, never expanded over candidates) and rows
+// 0..i of the candidate's own suffix K/V - in three sweeps: scores (lane per key), max/exp/sum, and the
 // weighted V sum (lane per output column, so V rows are read coalesced).
 //
 // Arithmetic type: fp64 when the tensors are f32 (this is the verification-grade path, whose
@@ -86,16 +86,21 @@ __global__ __launch_bounds__(64) void simple_kernel(Args a)
         qs[d] = (C)load_as_float(q + d);
     __syncthreads();
 
-    const T *kp = reinterpret_cast<const T *>(a.kp) + k * a.kp_sh;
-    const T *vp = reinterpret_cast<const T *>(a.vp) + k * a.kp_sh;
+    // the real prefix rows of the candidate's instruction: the last P of its a.P left-padded rows
+    const int n = b / a.C;
+    int P = a.plen ? a.plen[n] : a.P;
+    P = P < 0 ? 0 : (P > a.P ? a.P : P);
+    const long long poff = n * a.kp_sn + (long long)(a.P - P) * a.kp_sp + k * a.kp_sh;
+    const T *kp = reinterpret_cast<const T *>(a.kp) + poff;
+    const T *vp = reinterpret_cast<const T *>(a.vp) + poff;
     const T *ks = reinterpret_cast<const T *>(a.ks) + b * a.ks_sb + k * a.ks_sh;
     const T *vs = reinterpret_cast<const T *>(a.vs) + b * a.ks_sb + k * a.ks_sh;
-    const int nvis = a.P + i + 1; // whole prefix, then suffix rows 0..i
+    const int nvis = P + i + 1; // the instruction's real prefix rows, then suffix rows 0..i
 
     // sweep 1: scaled scores, one key per lane
     C mx = -INFINITY;
     for (int j = lane; j < nvis; j += 64) {
-        const T *kr = j < a.P ? kp + j * a.kp_sp : ks + (j - a.P) * a.ks_ss;
+        const T *kr = j < P ? kp + j * a.kp_sp : ks + (j - P) * a.ks_ss;
         C acc = 0;
         for (int d = 0; d < a.D; ++d)
             acc += qs[d] * (C)load_as_float(kr + d);
@@ -118,10 +123,10 @@ __global__ __launch_bounds__(64) void simple_kernel(Args a)
     // sweep 3: weighted sum of the visible V rows, one output column per lane
     for (int d = lane; d < a.D; d += 64) {
         C acc = 0;
-        for (int j = 0; j < a.P; ++j)
+        for (int j = 0; j < P; ++j)
             acc += sc[j] * (C)load_as_float(vp + j * a.kp_sp + d);
         for (int t = 0; t <= i; ++t)
-            acc += sc[a.P + t] * (C)load_as_float(vs + t * a.ks_ss + d);
+            acc += sc[P + t] * (C)load_as_float(vs + t * a.ks_ss + d);
         store_from(o + d, acc / den);
     }
     if (a.lse && lane == 0)

@@ -29,30 +29,31 @@ constexpr int kRing = 8;                   // tile slots in LDS
 constexpr int kSlotBytes = 2 * kTileBytes; // K image, then V image
 constexpr int kLdsBytes = kRing * kSlotBytes + kNW * kScrBytes;
 constexpr int kPassRows = kNW * kBlockRows;
+constexpr int kMinTiles = 6;                // shortest prefix, in tiles, that the pipelined pass takes
 
 typedef __attribute__((address_space(3))) int lds_int;
 
+// A pass is one (virtual head, group of 256 stacked rows) pair; a virtual head is one
+// (instruction, KV head) pair with its own prefix and its own C*S*G stacked rows.
 struct Pass {
-    int head, blk; // KV head; this wavefront's block (clamped to the last one)
-    bool active;   // the block exists
+    int vh, head, cand0; // virtual head = instruction * Hkv + KV head; first candidate of the instruction
+    int blk;             // this wavefront's block (clamped to the last one)
+    bool active;         // the block exists
 };
 
 __device__ inline Pass make_pass(const Args &a, int p, int npasses, int nblocks, int wave)
 {
     Pass ps;
     const int pc = p < npasses ? p : npasses - 1;
-    ps.head = pc % a.Hkv;
-    const int blk = (pc / a.Hkv) * kNW + wave;
+    const int VH = a.Np * a.Hkv;
+    ps.vh = pc % VH;
+    const int n = ps.vh / a.Hkv;
+    ps.head = ps.vh - n * a.Hkv;
+    ps.cand0 = n * a.C;
+    const int blk = (pc / VH) * kNW + wave;
     ps.active = p < npasses && blk < nblocks;
     ps.blk = blk < nblocks ? blk : nblocks - 1;
     return ps;
-}
-
-__device__ inline void set_head(const Args &a, Ctx &X, int head)
-{
-    X.head = head;
-    X.ksg = reinterpret_cast<const unsigned short *>(a.ks) + (long long)head * a.ks_sh;
-    X.vsg = reinterpret_cast<const unsigned short *>(a.vs) + (long long)head * a.ks_sh;
 }
 
 __device__ inline Ctx make_stream_ctx(const Args &a, lds_u8 *smem, int tid)
@@ -61,14 +62,14 @@ __device__ inline Ctx make_stream_ctx(const Args &a, lds_u8 *smem, int tid)
     X.lane = tid & 63;
     X.h = X.lane >> 5;
     X.c32 = X.lane & 31;
-    X.Mtot = a.B * a.S * a.G;
+    X.Mtot = a.C * a.S * a.G;
     X.c = a.scale * kLog2e;
     X.k_lane = smem + X.lane * 16;             // slot 0; slot s is kSlotBytes*s further
     X.v_lane = smem + kTileBytes + X.lane * 8;
     X.scr = smem + kRing * kSlotBytes + __builtin_amdgcn_readfirstlane(tid >> 6) * kScrBytes;
     X.sv_row_lo = 4 * ((X.c32 >> 4) & 1) + ((X.c32 >> 1) & 3);
     X.sv_chunk_lo = 2 * ((X.c32 >> 3) & 1) + (X.c32 & 1);
-    set_head(a, X, 0);
+    set_vhead(a, X, 0);
     return X;
 }
 
@@ -76,12 +77,11 @@ __device__ inline Ctx make_stream_ctx(const Args &a, lds_u8 *smem, int tid)
 // General pass: classic online softmax, tiles double-buffered in slots 0 and 1.  Every thread
 // of the workgroup must call it (barriers inside), whether or not its wavefront has a block.
 // ------------------------------------------------------------------------------------------
-__device__ __attribute__((always_inline)) void general_pass(const Args &a, Ctx &X, lds_u8 *smem, int tid, int ntiles,
-                                                       int head, int blk, bool active)
+__device__ __attribute__((always_inline)) void general_pass(const Args &a, Ctx &X, lds_u8 *smem, int tid, int vh, int blk,
+                                                            bool active)
 {
-    set_head(a, X, head);
-    const unsigned short *kpg = reinterpret_cast<const unsigned short *>(a.kp) + (long long)head * a.kp_sh;
-    const unsigned short *vpg = reinterpret_cast<const unsigned short *>(a.vp) + (long long)head * a.kp_sh;
+    set_vhead(a, X, vh);
+    const int ntiles = (X.P + kTileKeys - 1) / kTileKeys;
     const TileSlot t = make_tile_slot(tid);
     const int r0 = blk * kBlockRows;
     const Row row = decode_row(a, X, blk);
@@ -101,19 +101,19 @@ __device__ __attribute__((always_inline)) void general_pass(const Args &a, Ctx &
 
     if (ntiles > 0) {
         uintx4 kv, vv;
-        load_tile_chunks(a, kpg, vpg, t, 0, kv, vv);
+        load_tile_chunks(a, X, t, 0, kv, vv);
         __syncthreads(); // whatever the ring held has been used by every wavefront
-        write_tile_chunks(a, t, 0, smem, smem + kTileBytes, tid, kv, vv);
+        write_tile_chunks(X, t, 0, smem, smem + kTileBytes, tid, kv, vv);
         __syncthreads();
         for (int kt = 0; kt < ntiles; ++kt) {
             const int ktn = kt + 1 < ntiles ? kt + 1 : kt;
-            load_tile_chunks(a, kpg, vpg, t, ktn, kv, vv);
+            load_tile_chunks(a, X, t, ktn, kv, vv);
             if (work)
                 prefix_tile_classic(X, X.k_lane + (kt & 1) * kSlotBytes, X.v_lane + (kt & 1) * kSlotBytes,
-                                    a.P - kt * kTileKeys, q, st);
+                                    X.P - kt * kTileKeys, q, st);
             if (kt + 1 < ntiles) {
                 lds_u8 *slot = smem + ((kt + 1) & 1) * kSlotBytes;
-                write_tile_chunks(a, t, kt + 1, slot, slot + kTileBytes, tid, kv, vv);
+                write_tile_chunks(X, t, kt + 1, slot, slot + kTileBytes, tid, kv, vv);
             }
             __syncthreads();
         }
@@ -129,7 +129,7 @@ __device__ __attribute__((always_inline)) void general_pass(const Args &a, Ctx &
 }
 
 __global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
-void stream_general_kernel(Args a, int npasses, int ntiles)
+void stream_general_kernel(Args a, int npasses)
 {
     extern __shared__ __align__(16) unsigned char smem_generic[];
     lds_u8 *smem = (lds_u8 *)smem_generic;
@@ -139,7 +139,7 @@ void stream_general_kernel(Args a, int npasses, int ntiles)
     const int nblocks = (X.Mtot + kBlockRows - 1) / kBlockRows;
     for (int p = blockIdx.x; p < npasses; p += gridDim.x) {
         const Pass ps = make_pass(a, p, npasses, nblocks, wave);
-        general_pass(a, X, smem, tid, ntiles, ps.head, ps.blk, ps.active);
+        general_pass(a, X, smem, tid, ps.vh, ps.blk, ps.active);
     }
 }
 
@@ -180,7 +180,7 @@ __device__ inline void stage_load(const Stager &g, int kt, uintx4 &kv, uintx4 &v
 
 template <bool ONE_STEP>
 __global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
-void stream_pipelined_kernel(Args a, int npasses, int ntiles)
+void stream_pipelined_kernel(Args a, int npasses)
 {
     extern __shared__ __align__(16) unsigned char smem_generic[];
     lds_u8 *smem = (lds_u8 *)smem_generic;
@@ -188,7 +188,6 @@ void stream_pipelined_kernel(Args a, int npasses, int ntiles)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     Ctx X = make_stream_ctx(a, smem, tid);
     const int nblocks = (X.Mtot + kBlockRows - 1) / kBlockRows;
-    const int T = ntiles;
     auto kimg = [&](int t) { return X.k_lane + (t & (kRing - 1)) * kSlotBytes; };
     auto vimg = [&](int t) { return X.v_lane + (t & (kRing - 1)) * kSlotBytes; };
     auto stage_write = [&](int kt, const uintx4 &kv, const uintx4 &vv) {
@@ -198,29 +197,39 @@ void stream_pipelined_kernel(Args a, int npasses, int ntiles)
     };
 
     Stager g;
-    {
-        const TileSlot ts = make_tile_slot(tid);
-        const int nlast = a.P - (T - 1) * kTileKeys; // rows of the last tile, 1..32
-        const int kr = ts.k_row < nlast ? ts.k_row : nlast - 1, vr = ts.v_row < nlast ? ts.v_row : nlast - 1;
-        g.k_off = (unsigned)(ts.k_row * a.kp_sp + ts.k_chunk * 8) * 2u;
-        g.v_off = (unsigned)(ts.v_row * a.kp_sp + ts.v_chunk * 8) * 2u;
-        g.k_off_last = (unsigned)(kr * a.kp_sp + ts.k_chunk * 8) * 2u;
-        g.v_off_last = (unsigned)(vr * a.kp_sp + ts.v_chunk * 8) * 2u;
-        g.tile_stride = (unsigned)(kTileKeys * a.kp_sp) * 2u;
-        g.last = T - 1;
-    }
+    const TileSlot ts = make_tile_slot(tid);
+    g.k_off = (unsigned)(ts.k_row * a.kp_sp + ts.k_chunk * 8) * 2u;
+    g.v_off = (unsigned)(ts.v_row * a.kp_sp + ts.v_chunk * 8) * 2u;
+    g.tile_stride = (unsigned)(kTileKeys * a.kp_sp) * 2u;
 
     bool wg_bad = false;
     int p = blockIdx.x;
     Pass ps = make_pass(a, p, npasses, nblocks, wave);
-    Row nxt = decode_row(a, X, ps.blk, ps.head);
+    Row nxt = decode_row(a, X, ps.blk, ps.head, ps.cand0);
     uintx4 q[8]; // this pass's Q fragments until their last use, then the next pass's
     load_q(a, X, nxt, q);
 
+    bool wg_short = false;
     while (p < npasses) {
-        set_head(a, X, ps.head);
-        g.kbase = reinterpret_cast<const unsigned char *>(a.kp) + (long long)ps.head * a.kp_sh * 2;
-        g.vbase = reinterpret_cast<const unsigned char *>(a.vp) + (long long)ps.head * a.kp_sh * 2;
+        set_vhead(a, X, ps.vh);
+        const int T = (X.P + kTileKeys - 1) / kTileKeys;
+        if (T < kMinTiles) { // this instruction's prefix is too short for the pipeline: left to the general sweep below
+            wg_short = true;
+            p += gridDim.x;
+            ps = make_pass(a, p, npasses, nblocks, wave);
+            nxt = decode_row(a, X, ps.blk, ps.head, ps.cand0);
+            load_q(a, X, nxt, q);
+            continue;
+        }
+        {
+            const int nlast = X.P - (T - 1) * kTileKeys; // rows of the last tile, 1..32
+            const int kr = ts.k_row < nlast ? ts.k_row : nlast - 1, vr = ts.v_row < nlast ? ts.v_row : nlast - 1;
+            g.k_off_last = (unsigned)(kr * a.kp_sp + ts.k_chunk * 8) * 2u;
+            g.v_off_last = (unsigned)(vr * a.kp_sp + ts.v_chunk * 8) * 2u;
+            g.last = T - 1;
+            g.kbase = reinterpret_cast<const unsigned char *>(X.kpg);
+            g.vbase = reinterpret_cast<const unsigned char *>(X.vpg);
+        }
         const int blk = ps.blk, r0 = blk * kBlockRows;
         const bool active = ps.active;
         const Row row = nxt;
@@ -247,7 +256,7 @@ void stream_pipelined_kernel(Args a, int npasses, int ntiles)
         // the block's suffix: candidate sb, keys 0..skmax
         const int sb = (int)fdiv(fdiv(r0, a.div_g), a.div_s);
         const int i_hi = (int)fdiv(r0 + kBlockRows - 1, a.div_g) - sb * a.S;
-        const int len = len_uniform(a, sb);
+        const int len = len_uniform(a, X.cand0 + sb);
         const int skmax = i_hi < len - 1 ? i_hi : len - 1;
 
         // ---- first prefix tile: scores, reference maximum ----
@@ -302,12 +311,12 @@ void stream_pipelined_kernel(Args a, int npasses, int ntiles)
         if (t + 1 <= T - 2) {
             stage_write(t + 2, kv0, vv0);
             stage_write(t + 3, kv1, vv1);
-            load_suffix_k(a, X, sb, 0, skmax, skf);
+            load_suffix_k(a, X, X.cand0 + sb, 0, skmax, skf);
             __syncthreads();
             PSKV_STEP_PAIR(t);
             t += 2;
         } else {
-            load_suffix_k(a, X, sb, 0, skmax, skf);
+            load_suffix_k(a, X, X.cand0 + sb, 0, skmax, skf);
         }
 #undef PSKV_STEP_PAIR
         if (t <= T - 2) { // one step left over: do it and put scores and weights back in their places
@@ -317,14 +326,14 @@ void stream_pipelined_kernel(Args a, int npasses, int ntiles)
             pB[0] = pA[0];
             pB[1] = pA[1];
         }
-        if (a.P & (kTileKeys - 1)) { // ragged last prefix tile: keys past the prefix are not visible
-            const int nv = a.P - (T - 1) * kTileKeys - 4 * X.h;
+        if (X.P & (kTileKeys - 1)) { // ragged last prefix tile: keys past the prefix are not visible
+            const int nv = X.P - (T - 1) * kTileKeys - 4 * X.h;
 #pragma unroll
             for (int e = 0; e < 16; ++e)
                 if (8 * (e >> 2) + (e & 3) >= nv)
                     sA[e] = -INFINITY;
         }
-        load_suffix_v(a, X, sb, 0, skmax, svf); // one step ahead of its use
+        load_suffix_v(a, X, X.cand0 + sb, 0, skmax, svf); // one step ahead of its use
         // ---- last prefix tile: the "next scores" are those of the first suffix step ----
         pipe_tile<true, true, true, false, false, false, true>(kimg(0), skf, vimg(T - 2), kimg(0), vimg(T - 1), pre, q, sA,
                                                                sB, X.c, m, 0, l, pB, pA, o);
@@ -333,7 +342,7 @@ void stream_pipelined_kernel(Args a, int npasses, int ntiles)
         p += gridDim.x;
         ps = make_pass(a, p, npasses, nblocks, wave);
         if (ONE_STEP) { // Q has been used for the last time: the next pass's Q takes its place
-            nxt = decode_row(a, X, ps.blk, ps.head);
+            nxt = decode_row(a, X, ps.blk, ps.head, ps.cand0);
             load_q(a, X, nxt, q);
         }
 
@@ -345,8 +354,8 @@ void stream_pipelined_kernel(Args a, int npasses, int ntiles)
         pv_from_scratch(X, svf[1], as_bf16x8(pB[1]), o);
         if (!ONE_STEP) {
             for (int k0 = kTileKeys; k0 <= skmax; k0 += kTileKeys) {
-                load_suffix_k(a, X, sb, k0, skmax, skf);
-                load_suffix_v(a, X, sb, k0, skmax, svf);
+                load_suffix_k(a, X, X.cand0 + sb, k0, skmax, skf);
+                load_suffix_v(a, X, X.cand0 + sb, k0, skmax, svf);
 #pragma unroll
                 for (int e = 0; e < 16; ++e)
                     sB[e] = 0.f;
@@ -355,7 +364,7 @@ void stream_pipelined_kernel(Args a, int npasses, int ntiles)
                     sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(skf[ks]), as_bf16x8(q[ks]), sB, 0, 0, 0);
                 suffix_step_fixed(X, (int)row.ri, k0, sB, m, l, svf, o);
             }
-            nxt = decode_row(a, X, ps.blk, ps.head);
+            nxt = decode_row(a, X, ps.blk, ps.head, ps.cand0);
             load_q(a, X, nxt, q);
         }
 
@@ -370,13 +379,15 @@ void stream_pipelined_kernel(Args a, int npasses, int ntiles)
                                               0) != 0;
     }
 
-    // Rare: some row met scores far above its first tile's maximum.  Whatever this workgroup
-    // stored is replaced by the general path's result (kept out of the main loop so that it
-    // costs it no registers).
-    if (wg_bad)
+    // Rare: some row met scores far above its first tile's maximum; whatever this workgroup
+    // stored is then replaced by the general path's result.  The same sweep serves the passes
+    // skipped above.  (Kept out of the main loop so that it costs it no registers.)
+    if (wg_bad || wg_short)
         for (int p2 = blockIdx.x; p2 < npasses; p2 += gridDim.x) {
             const Pass ps2 = make_pass(a, p2, npasses, nblocks, wave);
-            general_pass(a, X, smem, tid, ntiles, ps2.head, ps2.blk, ps2.active);
+            set_vhead(a, X, ps2.vh);
+            if (wg_bad || (X.P + kTileKeys - 1) / kTileKeys < kMinTiles)
+                general_pass(a, X, smem, tid, ps2.vh, ps2.blk, ps2.active);
         }
 }
 
@@ -411,8 +422,8 @@ bool mfma_supported(const Args &a, int dtype)
 {
     if (dtype != 1 || a.D != kD)
         return false;
-    const long long rows = (long long)a.B * a.S * a.G;
-    const long long passes = ((rows + kPassRows - 1) / kPassRows) * a.Hkv;
+    const long long rows = (long long)a.C * a.S * a.G;
+    const long long passes = ((rows + kPassRows - 1) / kPassRows) * a.Np * a.Hkv;
     return rows <= 0x7fffffffLL - kPassRows && passes <= 0x7fffffffLL;
 }
 
@@ -427,20 +438,18 @@ hipError_t launch_stream(const Args &a, hipStream_t stream)
     const int num_cu = device_cu_count(e);
     if (e != hipSuccess)
         return e;
-    const int ntiles = (a.P + kTileKeys - 1) / kTileKeys;
-    const long long rows = (long long)a.B * a.S * a.G;
-    const long long npasses = ((rows + kPassRows - 1) / kPassRows) * a.Hkv;
+    const int max_tiles = (a.P + kTileKeys - 1) / kTileKeys;
+    const long long rows = (long long)a.C * a.S * a.G; // stacked rows of one virtual head
+    const long long npasses = ((rows + kPassRows - 1) / kPassRows) * a.Np * a.Hkv;
     const unsigned grid = (unsigned)(npasses < num_cu ? npasses : num_cu);
-    const bool pipelined = ((long long)a.S * a.G) % kBlockRows == 0 && ntiles >= 6 &&
+    const bool pipelined = ((long long)a.S * a.G) % kBlockRows == 0 && max_tiles >= kMinTiles &&
                            (long long)a.P * a.kp_sp * 2 < 0x7fffffffLL;
     if (!pipelined)
-        hipLaunchKernelGGL(stream_general_kernel, dim3(grid), dim3(kNW * 64), kLdsBytes, stream, a, (int)npasses, ntiles);
+        hipLaunchKernelGGL(stream_general_kernel, dim3(grid), dim3(kNW * 64), kLdsBytes, stream, a, (int)npasses);
     else if (a.S <= kTileKeys)
-        hipLaunchKernelGGL(stream_pipelined_kernel<true>, dim3(grid), dim3(kNW * 64), kLdsBytes, stream, a, (int)npasses,
-                           ntiles);
+        hipLaunchKernelGGL(stream_pipelined_kernel<true>, dim3(grid), dim3(kNW * 64), kLdsBytes, stream, a, (int)npasses);
     else
-        hipLaunchKernelGGL(stream_pipelined_kernel<false>, dim3(grid), dim3(kNW * 64), kLdsBytes, stream, a, (int)npasses,
-                           ntiles);
+        hipLaunchKernelGGL(stream_pipelined_kernel<false>, dim3(grid), dim3(kNW * 64), kLdsBytes, stream, a, (int)npasses);
     return hipGetLastError();
 }
 

@@ -159,3 +159,121 @@ def make_inputs(w: Workload, pad: str = "nan", seed: Optional[int] = None,
 
 def custom_workload(name, B, P, S, len_lo, len_hi, Hq, Hkv, D, dtype, index=100) -> Workload:
     return Workload(name, B, P, S, len_lo, len_hi, Hq, Hkv, D, dtype, index)
+
+
+# ---------------------------------------------------------------------------------------------
+# Batched multi-instruction form (Sec. 4.3 of the paper): Np instructions with their own
+# left-padded prefixes and C candidates each.
+# ---------------------------------------------------------------------------------------------
+@dataclass(frozen=True)
+class MultiWorkload:
+    name: str
+    Np: int              # instructions
+    C: int               # candidates per instruction (B = Np * C)
+    P: int               # padded prefix length
+    pre_lo: int          # real prefix lengths drawn uniformly in [pre_lo, pre_hi]
+    pre_hi: int
+    S: int
+    len_lo: int
+    len_hi: int
+    Hq: int
+    Hkv: int
+    D: int
+    dtype: str
+    index: int
+
+    @property
+    def B(self) -> int:
+        return self.Np * self.C
+
+    @property
+    def G(self) -> int:
+        return self.Hq // self.Hkv
+
+    @property
+    def seed(self) -> int:
+        return BASE_SEED + 1000 + self.index
+
+
+MULTI_WORKLOADS: Dict[str, MultiWorkload] = {w.name: w for w in [
+    # 8 instructions of 78-250 prompt tokens (Sec. 3: prompts of roughly 80 tokens plus the chat
+    # template), 128 candidates each, the 8B-class GQA head layout
+    MultiWorkload("multi8_gqa8b_bf16",  8, 128, 256,  96, 256, 24, 16, 24, 32, 8, 128, "bf16", 0),
+    # 32 instructions, 32 candidates each (more virtual heads than one pass of workgroups)
+    MultiWorkload("multi32_gqa8b_bf16", 32, 32, 256,  96, 256, 24, 16, 24, 32, 8, 128, "bf16", 1),
+    # long, unevenly padded prefixes streamed through LDS
+    MultiWorkload("multi4_long_bf16",   4,  64, 1024, 300, 1024, 32, 32, 32, 32, 8, 128, "bf16", 2),
+]}
+
+
+@dataclass
+class MultiInputs:
+    w: MultiWorkload
+    q: np.ndarray        # [B,S,Hq,D]
+    k_suf: np.ndarray    # [B,S,Hkv,D]
+    v_suf: np.ndarray
+    k_pre: np.ndarray    # [Np,P,Hkv,D], left-padded
+    v_pre: np.ndarray
+    pre_len: np.ndarray  # [Np] int32
+    suf_len: np.ndarray  # [B] int32
+    scale: float
+    meta: dict = field(default_factory=dict)
+
+    def take_instructions(self, which: np.ndarray) -> "MultiInputs":
+        """The same problem restricted to the listed instructions and all their candidates."""
+        which = np.asarray(which, dtype=np.int64)
+        cand = (which[:, None] * self.w.C + np.arange(self.w.C)[None, :]).reshape(-1)
+        w = MultiWorkload(self.w.name + "_subset", len(which), self.w.C, self.w.P, self.w.pre_lo, self.w.pre_hi,
+                          self.w.S, self.w.len_lo, self.w.len_hi, self.w.Hq, self.w.Hkv, self.w.D, self.w.dtype,
+                          self.w.index)
+        c = np.ascontiguousarray
+        return MultiInputs(w, c(self.q[cand]), c(self.k_suf[cand]), c(self.v_suf[cand]), c(self.k_pre[which]),
+                           c(self.v_pre[which]), c(self.pre_len[which]), c(self.suf_len[cand]), self.scale,
+                           dict(self.meta, instructions=which))
+
+
+def make_multi_inputs(w: MultiWorkload, pad: str = "nan", seed: Optional[int] = None) -> MultiInputs:
+    """Draw one multi-instruction problem.  Streams (children of ``SeedSequence(seed)``): child 0
+    draws pre_len then suf_len (uniform integers, inclusive), child 1 draws k_pre then v_pre,
+    child 2+n draws q, k_suf, v_suf of the n-th block of 64 candidates.  N(0,1) float32 draws,
+    rounded to bf16 (RNE) for bf16 workloads.  Prefix rows before an instruction's real rows
+    and suffix rows at or beyond a candidate's length are padding: NaN for pad="nan", 0 for
+    pad="zero", the draws themselves for pad="keep"."""
+    nblk = (w.B + CAND_BLOCK - 1) // CAND_BLOCK
+    children = np.random.SeedSequence(w.seed if seed is None else seed).spawn(2 + nblk)
+    rng0 = np.random.default_rng(children[0])
+    pre_len = rng0.integers(w.pre_lo, w.pre_hi + 1, size=w.Np, dtype=np.int64).astype(np.int32)
+    suf_len = rng0.integers(w.len_lo, w.len_hi + 1, size=w.B, dtype=np.int64).astype(np.int32)
+    bf16 = w.dtype == "bf16"
+    store = np.uint16 if bf16 else np.float32
+    fill = {"nan": np.float32(np.nan), "zero": np.float32(0.0)}.get(pad)
+
+    def finish(a):
+        return f32_to_bf16_bits(a) if bf16 else a
+
+    rng_p = np.random.default_rng(children[1])
+    pre_pad = np.arange(w.P)[None, :] < (w.P - pre_len)[:, None]     # [Np,P]: True on left padding
+    pre = []
+    for _ in range(2):
+        a = rng_p.standard_normal(size=(w.Np, w.P, w.Hkv, w.D), dtype=np.float32)
+        if fill is not None:
+            a[pre_pad] = fill
+        pre.append(finish(a))
+    q = np.empty((w.B, w.S, w.Hq, w.D), dtype=store)
+    k_suf = np.empty((w.B, w.S, w.Hkv, w.D), dtype=store)
+    v_suf = np.empty((w.B, w.S, w.Hkv, w.D), dtype=store)
+    for n in range(nblk):
+        lo, hi = n * CAND_BLOCK, min(w.B, (n + 1) * CAND_BLOCK)
+        rng = np.random.default_rng(children[2 + n])
+        padded = np.arange(w.S)[None, :] >= suf_len[lo:hi, None]
+        for dst, heads in ((q, w.Hq), (k_suf, w.Hkv), (v_suf, w.Hkv)):
+            a = rng.standard_normal(size=(hi - lo, w.S, heads, w.D), dtype=np.float32)
+            if fill is not None:
+                a[padded] = fill
+            dst[lo:hi] = finish(a)
+    scale = float(np.float32(1.0 / np.sqrt(w.D)))
+    return MultiInputs(w, q, k_suf, v_suf, pre[0], pre[1], pre_len, suf_len, scale, {"pad": pad})
+
+
+def custom_multi_workload(name, Np, C, P, pre_lo, pre_hi, S, len_lo, len_hi, Hq, Hkv, D, dtype, index=100):
+    return MultiWorkload(name, Np, C, P, pre_lo, pre_hi, S, len_lo, len_hi, Hq, Hkv, D, dtype, index)

@@ -87,3 +87,22 @@ def compare_lse(got: np.ndarray, ref: np.ndarray, suf_len: np.ndarray, dtype: st
         err = np.abs(got[valid] - ref[valid]).max()
         tol = 1e-5 if dtype == "f32" else 2e-2
         assert err <= tol * max(1.0, np.abs(ref[valid]).max()), f"{what}: lse error {err:.3e}"
+
+
+def to_device_multi(inp: "gen.MultiInputs", device="cuda:0"):
+    import torch
+
+    def dev(a):
+        t = torch.from_numpy(np.ascontiguousarray(a))
+        if inp.w.dtype == "bf16":
+            t = t.view(torch.bfloat16)
+        return t.to(device)
+
+    return dict(q=dev(inp.q), k_suf=dev(inp.k_suf), v_suf=dev(inp.v_suf), k_pre=dev(inp.k_pre),
+                v_pre=dev(inp.v_pre), pre_len=torch.from_numpy(inp.pre_len).to(device),
+                suf_len=torch.from_numpy(inp.suf_len).to(device))
+
+
+def oracle_out_multi(inp: "gen.MultiInputs", want_lse=False):
+    return orc.attn_multi(inp.q, inp.k_suf, inp.v_suf, inp.k_pre, inp.v_pre, inp.pre_len, inp.suf_len,
+                          inp.scale, inp.w.dtype, want_lse=want_lse)

@@ -106,6 +106,32 @@ def test_fwd_refuses_null_and_misaligned_pointers_before_any_launch():
     assert rc == pk.PSKV_ERR_INVALID_ARG
 
 
+def test_multi_params_layout_and_host_validation():
+    """The multi-instruction struct is the single-prefix struct plus three fields; its rules are
+    checked on the host: B a multiple of Np, Np >= 1, reserved 0, a prefix stride that holds a prefix."""
+    assert ctypes.sizeof(pk.pskv_multi_params) == ctypes.sizeof(pk.pskv_attn_params) + 16
+    assert pk.pskv_multi_params.Np.offset == ctypes.sizeof(pk.pskv_attn_params)
+    base = ok(B=8, dtype="bf16", D=128)
+    assert pk.pskv_attn_multi_validate(pk.make_multi_params(base, 4)) == pk.PSKV_OK
+    assert pk.pskv_attn_multi_validate(pk.make_multi_params(base, 1)) == pk.PSKV_OK
+    for np_, stride, needle in ((3, 0, "multiple of Np"), (0, 0, "at least 1"), (-2, 0, "at least 1"),
+                                (2, 48 * 4 * 128 - 8, "smaller than one prefix"), (2, 12345, "16 bytes"),
+                                (2, -8, "negative")):
+        st = pk.pskv_attn_multi_validate(pk.make_multi_params(base, np_, stride))
+        assert st == pk.PSKV_ERR_INVALID_ARG and needle in pk.pskv_last_error(), (np_, stride, pk.pskv_last_error())
+    p = pk.make_multi_params(base, 2, 48 * 4 * 128 + 64)
+    assert pk.pskv_attn_multi_validate(p) == pk.PSKV_OK
+    p.reserved = 1
+    assert pk.pskv_attn_multi_validate(p) == pk.PSKV_ERR_INVALID_ARG
+    # a forward call with bad arguments is refused before anything could be launched
+    lib = pk.load()
+    rc = lib.pskv_attn_fwd_multi(ctypes.byref(pk.make_multi_params(base, 4)), None, None, None, None, None, None,
+                                 None, None, None, None, 0, None)
+    assert rc == pk.PSKV_ERR_INVALID_ARG and "must not be NULL" in pk.pskv_last_error()
+    rc = lib.pskv_attn_fwd_multi(None, None, None, None, None, None, None, None, None, None, None, 0, None)
+    assert rc == pk.PSKV_ERR_INVALID_ARG
+
+
 def test_product_path_does_not_import_the_oracle():
     """No file of the package imports, links or loads anything of the CPU oracle."""
     pkg = os.path.join(ROOT, "paper_2603_13420_amd")
