@@ -29,7 +29,7 @@ constexpr int kRing = 8;                   // tile slots in LDS
 constexpr int kSlotBytes = 2 * kTileBytes; // K image, then V image
 constexpr int kLdsBytes = kRing * kSlotBytes + kNW * kScrBytes;
 constexpr int kPassRows = kNW * kBlockRows;
-constexpr int kMinTiles = 6;                // shortest prefix, in tiles, that the pipelined pass takes
+constexpr int kMinTiles = 3;                // shortest prefix, in tiles, that the pipelined pass takes
 
 typedef __attribute__((address_space(3))) int lds_int;
 
@@ -145,7 +145,7 @@ void stream_general_kernel(Args a, int npasses)
 
 // ------------------------------------------------------------------------------------------
 // Pipelined passes.  Preconditions (checked by the launcher): S*G is a multiple of 32, so a
-// 32-row block lies inside one candidate; the prefix has at least six tiles; one head's prefix
+// 32-row block lies inside one candidate; the padded prefix has at least three tiles; one head's prefix
 // spans less than 2^31 bytes, so tile addresses are a scalar base plus a 32-bit lane offset.
 // ONE_STEP: S <= 32, the suffix is a single 32-key step.
 //
@@ -429,7 +429,14 @@ bool mfma_supported(const Args &a, int dtype)
 
 hipError_t launch_mfma(const Args &a, hipStream_t stream)
 {
-    return resident_supported(a) ? launch_resident(a, stream) : launch_stream(a, stream);
+    // Suffix-side segments longer than one 32-key step (suffix, template and target together,
+    // Sec. 3) go to the streamed kernel whenever its pipelined pass applies: it runs every
+    // suffix step against the fixed reference, the resident kernels would fall back to their
+    // general path for such shapes.
+    const int max_tiles = (a.P + kTileKeys - 1) / kTileKeys;
+    const bool long_suffix = a.S > kTileKeys && ((long long)a.S * a.G) % kBlockRows == 0 && max_tiles >= kMinTiles &&
+                             (long long)a.P * a.kp_sp * 2 < 0x7fffffffLL;
+    return resident_supported(a) && !long_suffix ? launch_resident(a, stream) : launch_stream(a, stream);
 }
 
 hipError_t launch_stream(const Args &a, hipStream_t stream)
