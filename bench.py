@@ -50,6 +50,8 @@ def alg_counts(w, suf_len, pre_len=None):
 # Offline measurements: the commands and raw readings are in profiles/*_hbm_traffic.txt.
 HBM_TRAFFIC = {
     "gqa8b_bf16": {"fetch_kib": 145320.0, "fetch_scale": 2.0, "write_kib": 205771.0, "write_scale": 1.0},
+    "longprefix_bf16": {"fetch_kib": 63436.0, "fetch_scale": 2.0, "write_kib": 67074.0, "write_scale": 1.0},
+    "multi8_gqa8b_bf16": {"fetch_kib": 147373.0, "fetch_scale": 2.0, "write_kib": 208369.0, "write_scale": 1.0},
 }
 
 
