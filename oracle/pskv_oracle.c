@@ -273,3 +273,122 @@ int pskv_oracle_attn_multi(int Np, int C, int S, int Pp, int Hq, int Hkv, int D,
     }
     return failed ? 2 : 0;
 }
+
+/*
+ * Backward pass of the single-prefix form with respect to the suffix side (the paper keeps the
+ * computation graph of the suffix/target segment intact so that gradient-based synthesis can
+ * differentiate through cached execution, Sec. 1 and Sec. 4.2; the prefix K/V is a constant).
+ *
+ * Definition: with out = f(q, k_suf, v_suf) the forward pass above and dout a given tensor of
+ * the same shape, the result is the gradient of  L = sum(dout * out)  with respect to q, k_suf
+ * and v_suf.  It is written here as the textbook derivative of Eq. 2, row by row: for a valid
+ * query row with probabilities p_j over its visible rows (own copy of the prefix, then suffix
+ * rows 0..i),
+ *     dp_j = <dout_row, V_j>,   ds_j = p_j * (dp_j - sum_k p_k dp_k),
+ *     dq_row += scale * sum_j ds_j K_j,   dK_j += scale * ds_j q_row,   dV_j += p_j dout_row,
+ * where only the suffix rows j receive dK, dV (summed over the query heads that share the KV
+ * head).  Padded query rows contribute nothing and get dq = 0; padded suffix rows get 0.
+ * Not thread-parallel over candidates' shared outputs: one thread per candidate.
+ */
+int pskv_oracle_attn_bwd(int B, int S, int P, int Hq, int Hkv, int D, int dtype, double scale,
+                         const void *q, const void *k_suf, const void *v_suf,
+                         const void *k_pre, const void *v_pre, const int32_t *suf_len,
+                         const double *dout, double *dq, double *dk_suf, double *dv_suf, int nthreads)
+{
+    if (B < 0 || S < 1 || P < 0 || Hq < 1 || Hkv < 1 || D < 1 || Hq % Hkv != 0)
+        return 1;
+    if (dtype < 0 || dtype > 2 || !dout || !dq || !dk_suf || !dv_suf || !q || !k_suf || !v_suf ||
+        (P > 0 && (!k_pre || !v_pre)))
+        return 1;
+    for (int b = 0; b < B; ++b)
+        if (suf_len && (suf_len[b] < 0 || suf_len[b] > S))
+            return 1;
+    const int G = Hq / Hkv;
+    int failed = 0;
+#ifdef _OPENMP
+    if (nthreads > 0)
+        omp_set_num_threads(nthreads);
+#else
+    (void)nthreads;
+#endif
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int b = 0; b < B; ++b) {
+        const int len = suf_len ? suf_len[b] : S;
+        const int64_t T = (int64_t)P + len;
+        double *Kfull = (double *)malloc(sizeof(double) * (size_t)(T > 0 ? T : 1) * D);
+        double *Vfull = (double *)malloc(sizeof(double) * (size_t)(T > 0 ? T : 1) * D);
+        double *p = (double *)malloc(sizeof(double) * (size_t)(T > 0 ? T : 1));
+        double *dp = (double *)malloc(sizeof(double) * (size_t)(T > 0 ? T : 1));
+        if (!Kfull || !Vfull || !p || !dp) {
+#pragma omp atomic write
+            failed = 1;
+            free(Kfull); free(Vfull); free(p); free(dp);
+            continue;
+        }
+        for (int64_t x = 0; x < (int64_t)S * Hq * D; ++x)
+            dq[(int64_t)b * S * Hq * D + x] = 0.0;
+        for (int64_t x = 0; x < (int64_t)S * Hkv * D; ++x) {
+            dk_suf[(int64_t)b * S * Hkv * D + x] = 0.0;
+            dv_suf[(int64_t)b * S * Hkv * D + x] = 0.0;
+        }
+        for (int k = 0; k < Hkv; ++k) {
+            /* this candidate's private cache: copy of the prefix, then its suffix rows (Eq. 3) */
+            for (int64_t j = 0; j < P; ++j)
+                for (int d = 0; d < D; ++d) {
+                    Kfull[j * D + d] = widen(k_pre, (j * Hkv + k) * D + d, dtype);
+                    Vfull[j * D + d] = widen(v_pre, (j * Hkv + k) * D + d, dtype);
+                }
+            for (int64_t t = 0; t < len; ++t)
+                for (int d = 0; d < D; ++d) {
+                    const int64_t src = (((int64_t)b * S + t) * Hkv + k) * D + d;
+                    Kfull[(P + t) * D + d] = widen(k_suf, src, dtype);
+                    Vfull[(P + t) * D + d] = widen(v_suf, src, dtype);
+                }
+            for (int g = 0; g < G; ++g) {
+                const int h = k * G + g;
+                for (int i = 0; i < len; ++i) {
+                    const int64_t nvis = (int64_t)P + i + 1;
+                    const int64_t roff = (((int64_t)b * S + i) * Hq + h) * D;
+                    double m = -INFINITY;
+                    for (int64_t j = 0; j < nvis; ++j) {
+                        double acc = 0.0;
+                        for (int d = 0; d < D; ++d)
+                            acc += widen(q, roff + d, dtype) * Kfull[j * D + d];
+                        p[j] = acc * scale;
+                        if (p[j] > m)
+                            m = p[j];
+                    }
+                    double denom = 0.0;
+                    for (int64_t j = 0; j < nvis; ++j) {
+                        p[j] = exp(p[j] - m);
+                        denom += p[j];
+                    }
+                    double mean_dp = 0.0; /* sum_k p_k dp_k */
+                    for (int64_t j = 0; j < nvis; ++j) {
+                        p[j] /= denom;
+                        double acc = 0.0;
+                        for (int d = 0; d < D; ++d)
+                            acc += dout[roff + d] * Vfull[j * D + d];
+                        dp[j] = acc;
+                        mean_dp += p[j] * acc;
+                    }
+                    for (int64_t j = 0; j < nvis; ++j) {
+                        const double ds = p[j] * (dp[j] - mean_dp);
+                        for (int d = 0; d < D; ++d)
+                            dq[roff + d] += scale * ds * Kfull[j * D + d];
+                        if (j >= P) { /* a suffix row of this candidate */
+                            const int64_t koff = (((int64_t)b * S + (j - P)) * Hkv + k) * D;
+                            for (int d = 0; d < D; ++d) {
+                                dk_suf[koff + d] += scale * ds * widen(q, roff + d, dtype);
+                                dv_suf[koff + d] += p[j] * dout[roff + d];
+                            }
+                        }
+                    }
+                }
+            }
+        }
+        free(Kfull); free(Vfull); free(p); free(dp);
+    }
+    return failed ? 2 : 0;
+}

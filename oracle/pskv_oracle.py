@@ -47,6 +47,9 @@ def _load():
         lib.pskv_oracle_attn_multi.restype = ctypes.c_int
         lib.pskv_oracle_attn_multi.argtypes = [ctypes.c_int] * 8 + [ctypes.c_double] + \
             [ctypes.c_void_p] * 10 + [ctypes.c_int]
+        lib.pskv_oracle_attn_bwd.restype = ctypes.c_int
+        lib.pskv_oracle_attn_bwd.argtypes = [ctypes.c_int] * 7 + [ctypes.c_double] + \
+            [ctypes.c_void_p] * 10 + [ctypes.c_int]
         lib.pskv_oracle_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -99,6 +102,34 @@ def attn(q, k_suf, v_suf, k_pre, v_pre, suf_len, scale: float, dtype: str,
     if want_probs:
         res += (probs,)
     return res[0] if len(res) == 1 else res
+
+
+def attn_bwd(q, k_suf, v_suf, k_pre, v_pre, suf_len, dout, scale: float, dtype: str, nthreads: int = 0):
+    """Gradient of sum(dout * attn(...)) with respect to q, k_suf, v_suf (prefix constant).
+    dout is float64 [B,S,Hq,D].  Returns (dq, dk_suf, dv_suf), float64."""
+    B, S, Hq, D = q.shape
+    Hkv = k_suf.shape[2]
+    P = k_pre.shape[0]
+    q = _check(q, (B, S, Hq, D), dtype, "q")
+    k_suf = _check(k_suf, (B, S, Hkv, D), dtype, "k_suf")
+    v_suf = _check(v_suf, (B, S, Hkv, D), dtype, "v_suf")
+    k_pre = _check(k_pre, (P, Hkv, D), dtype, "k_pre")
+    v_pre = _check(v_pre, (P, Hkv, D), dtype, "v_pre")
+    dout = _check(dout, (B, S, Hq, D), "f64", "dout")
+    sl = None if suf_len is None else np.ascontiguousarray(suf_len, dtype=np.int32)
+    dq = np.empty((B, S, Hq, D), dtype=np.float64)
+    dk = np.empty((B, S, Hkv, D), dtype=np.float64)
+    dv = np.empty((B, S, Hkv, D), dtype=np.float64)
+
+    def ptr(a):
+        return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+    rc = _load().pskv_oracle_attn_bwd(B, S, P, Hq, Hkv, D, _DT[dtype], float(scale),
+                                      ptr(q), ptr(k_suf), ptr(v_suf), ptr(k_pre), ptr(v_pre), ptr(sl),
+                                      ptr(dout), ptr(dq), ptr(dk), ptr(dv), int(nthreads))
+    if rc != 0:
+        raise RuntimeError(f"pskv_oracle_attn_bwd failed with code {rc}")
+    return dq, dk, dv
 
 
 def attn_multi(q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, scale: float, dtype: str,
