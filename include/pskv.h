@@ -184,6 +184,39 @@ pskv_status pskv_attn_fwd_multi(const pskv_multi_params *p,
                                 void *workspace, size_t workspace_bytes,
                                 void *hip_stream);
 
+/*
+ * Backward pass of pskv_attn_fwd with respect to the suffix side.  The paper's cache keeps the
+ * suffix/target segment in the computation graph so that gradient-based suffix synthesis can
+ * differentiate through cached execution (Sec. 1, Sec. 4.2); the prefix K/V is a constant and
+ * gets no gradient.  Given dout = dL/dout, this computes, for L any function of out,
+ *
+ *     dq = dL/dq,   dk_suf = dL/dk_suf,   dv_suf = dL/dv_suf
+ *
+ * by the derivative of Eq. 2 (with p_j the softmax weights of a query row over its visible
+ * rows: ds_j = p_j (<dout_row, V_j> - <dout_row, out_row>), dq_row = scale sum_j ds_j K_j,
+ * dK_j = scale sum_rows ds_j q_row, dV_j = sum_rows p_j dout_row; suffix rows only, summed over
+ * the query heads that share the KV head).
+ *
+ *   q, k_suf, v_suf, k_pre, v_pre, suf_len   as for pskv_attn_fwd (same params struct)
+ *   out   [B,S,Hq,D]  device, read-only: the forward result
+ *   lse   [B,Hq,S]    device, read-only, REQUIRED: the forward log-sum-exp
+ *   dout  [B,S,Hq,D]  device, read-only, laid out like out (o_stride_*)
+ *   dq    [B,S,Hq,D]  device, written in full, laid out like q (q_stride_*); padded rows = 0
+ *   dk_suf, dv_suf [B,S,Hkv,D] device, written in full, laid out like k_suf; padded rows = 0
+ *
+ * Padded rows of dout are ignored.  Same ownership, stream and error rules as the forward call;
+ * outputs must not alias inputs or one another.  p->impl: AUTO and SIMPLE select the vector-ALU
+ * kernels (fp64 arithmetic for f32 tensors, fp32 for bf16); MFMA is refused in this version.
+ */
+pskv_status pskv_attn_bwd(const pskv_attn_params *p,
+                          const void *q, const void *k_suf, const void *v_suf,
+                          const void *k_pre, const void *v_pre,
+                          const int32_t *suf_len,
+                          const void *out, const float *lse, const void *dout,
+                          void *dq, void *dk_suf, void *dv_suf,
+                          void *workspace, size_t workspace_bytes,
+                          void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

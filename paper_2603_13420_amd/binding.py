@@ -19,7 +19,7 @@ _IMPL = {"auto": PSKV_IMPL_AUTO, "simple": PSKV_IMPL_SIMPLE, "mfma": PSKV_IMPL_M
 
 EXPORTS = ["pskv_version", "pskv_status_str", "pskv_last_error", "pskv_attn_fwd_workspace_bytes",
            "pskv_attn_validate", "pskv_attn_fwd", "pskv_attn_fwd_timed",
-           "pskv_attn_multi_validate", "pskv_attn_fwd_multi"]
+           "pskv_attn_multi_validate", "pskv_attn_fwd_multi", "pskv_attn_bwd"]
 
 
 class pskv_attn_params(ctypes.Structure):
@@ -75,6 +75,8 @@ def load():
     lib.pskv_attn_multi_validate.argtypes = [PM]
     lib.pskv_attn_fwd_multi.restype = ctypes.c_int
     lib.pskv_attn_fwd_multi.argtypes = [PM, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    lib.pskv_attn_bwd.restype = ctypes.c_int
+    lib.pskv_attn_bwd.argtypes = [P] + [vp] * 13 + [ctypes.c_size_t, vp]
     _lib = lib
     return lib
 
@@ -297,3 +299,35 @@ class PreparedMultiCall:
         rc = self._fn(*self._args)
         if rc != PSKV_OK:
             _raise(rc)
+
+
+def pskv_attn_bwd(q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse, dout, dq=None, dk_suf=None, dv_suf=None,
+                  impl: str = "auto", scale: float = 0.0, stream: Optional[int] = None):
+    """Enqueue the backward pass (gradients with respect to q, k_suf, v_suf; the prefix is a
+    constant).  out and lse are the forward results; dout is laid out like out.  Gradient
+    tensors are allocated by torch when not given (dq like q, dk_suf/dv_suf like k_suf).
+    Returns (dq, dk_suf, dv_suf)."""
+    import torch
+    if lse is None:
+        raise ValueError("the backward pass needs the forward pass's lse")
+    _check_inputs(q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse)
+    if tuple(dout.shape) != tuple(out.shape) or dout.stride() != out.stride() or dout.dtype != q.dtype:
+        raise ValueError("dout must have the shape, strides and dtype of out")
+    dq = torch.empty_like(q) if dq is None else dq
+    dk_suf = torch.empty_like(k_suf) if dk_suf is None else dk_suf
+    dv_suf = torch.empty_like(v_suf) if dv_suf is None else dv_suf
+    if dq.shape != q.shape or dq.stride() != q.stride() or dq.dtype != q.dtype:
+        raise ValueError("dq must have the shape, strides and dtype of q")
+    for name, t in (("dk_suf", dk_suf), ("dv_suf", dv_suf)):
+        if t.shape != k_suf.shape or t.stride() != k_suf.stride() or t.dtype != q.dtype:
+            raise ValueError(f"{name} must have the shape, strides and dtype of k_suf")
+    p = _params_from_tensors(q, k_suf, k_pre, out, impl, scale)
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    with torch.cuda.device(q.device):
+        rc = load().pskv_attn_bwd(ctypes.byref(p), _ptr(q), _ptr(k_suf), _ptr(v_suf), _ptr(k_pre), _ptr(v_pre),
+                                  _ptr(suf_len), _ptr(out), _ptr(lse), _ptr(dout), _ptr(dq), _ptr(dk_suf),
+                                  _ptr(dv_suf), None, 0, ctypes.c_void_p(stream))
+    if rc != PSKV_OK:
+        _raise(rc)
+    return dq, dk_suf, dv_suf

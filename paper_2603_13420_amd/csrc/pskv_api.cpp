@@ -224,6 +224,59 @@ pskv_status pskv_attn_fwd_multi(const pskv_multi_params *p, const void *q, const
                   hip_stream);
 }
 
+pskv_status pskv_attn_bwd(const pskv_attn_params *p, const void *q, const void *k_suf, const void *v_suf,
+                          const void *k_pre, const void *v_pre, const int32_t *suf_len, const void *out,
+                          const float *lse, const void *dout, void *dq, void *dk_suf, void *dv_suf,
+                          void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    (void)workspace;
+    (void)workspace_bytes; // no path needs scratch
+    pskv::BwdArgs g{};
+    pskv::Args &a = g.f;
+    bool use_mfma = false;
+    pskv_status s = resolve(p, 1, 0, a, use_mfma);
+    if (s != PSKV_OK)
+        return s;
+    if (p->impl == PSKV_IMPL_MFMA)
+        return fail(PSKV_ERR_UNSUPPORTED, "the backward pass has no MFMA path in this version");
+    if (pskv::bwd_simple_lds_bytes(a, p->dtype) > kSimpleMaxLds)
+        return fail(PSKV_ERR_UNSUPPORTED, "the backward pass keeps one score row in LDS: P+S+2D=%d is too large",
+                    p->P + p->S + 2 * p->D);
+    if (!q || !k_suf || !v_suf || !out || !lse || !dout || !dq || !dk_suf || !dv_suf)
+        return fail(PSKV_ERR_INVALID_ARG, "q, k_suf, v_suf, out, lse, dout, dq, dk_suf and dv_suf must not be NULL");
+    if (a.P > 0 && (!k_pre || !v_pre))
+        return fail(PSKV_ERR_INVALID_ARG, "k_pre and v_pre must not be NULL when P > 0");
+    const void *ptrs[] = {q, k_suf, v_suf, k_pre, v_pre, out, dout, dq, dk_suf, dv_suf};
+    for (const void *ptr : ptrs)
+        if (misaligned(ptr))
+            return fail(PSKV_ERR_INVALID_ARG, "data pointer %p is not 16-byte aligned", ptr);
+    if ((reinterpret_cast<uintptr_t>(suf_len) & 3u) || (reinterpret_cast<uintptr_t>(lse) & 3u))
+        return fail(PSKV_ERR_INVALID_ARG, "suf_len and lse must be 4-byte aligned");
+    const void *ins[] = {q, k_suf, v_suf, k_pre, v_pre, out, dout, lse};
+    void *outs[] = {dq, dk_suf, dv_suf};
+    for (int x = 0; x < 3; ++x) {
+        for (const void *in : ins)
+            if (outs[x] == in)
+                return fail(PSKV_ERR_INVALID_ARG, "a gradient output must not alias an input");
+        for (int y = x + 1; y < 3; ++y)
+            if (outs[x] == outs[y])
+                return fail(PSKV_ERR_INVALID_ARG, "gradient outputs must not alias one another");
+    }
+    a.q = q; a.ks = k_suf; a.vs = v_suf; a.kp = k_pre; a.vp = v_pre;
+    a.len = suf_len;
+    a.out = const_cast<void *>(out); // read-only in every backward kernel
+    a.lse = const_cast<float *>(lse);
+    g.dout = dout; g.dq = dq; g.dk = dk_suf; g.dv = dv_suf;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = pskv::launch_bwd_dq_simple(g, p->dtype, stream);
+    if (e == hipSuccess)
+        e = pskv::launch_bwd_dkv_simple(g, p->dtype, stream);
+    if (e != hipSuccess)
+        return fail(PSKV_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+    g_err[0] = '\0';
+    return PSKV_OK;
+}
+
 pskv_status pskv_attn_fwd_timed(const pskv_attn_params *p, const void *q, const void *k_suf,
                                 const void *v_suf, const void *k_pre, const void *v_pre,
                                 const int32_t *suf_len, void *out, float *lse, void *workspace,

@@ -44,6 +44,18 @@ struct Args {
     long long o_sb, o_ss, o_sh;
 };
 
+// Backward pass: the forward problem (f.out and f.lse are the forward results, read-only here),
+// the incoming gradient dout (laid out like out) and the three outputs (dq like q; dk, dv like
+// k_suf, v_suf).
+struct BwdArgs {
+    Args f;
+    const void *dout;
+    void *dq, *dk, *dv;
+};
+size_t bwd_simple_lds_bytes(const Args &a, int dtype);
+hipError_t launch_bwd_dq_simple(const BwdArgs &g, int dtype, hipStream_t stream);
+hipError_t launch_bwd_dkv_simple(const BwdArgs &g, int dtype, hipStream_t stream);
+
 // Simple path: one wavefront per query row. dtype 0 = f32 storage (fp64 arithmetic),
 // 1 = bf16 storage (fp32 arithmetic). Returns the HIP launch status.
 hipError_t launch_simple(const Args &a, int dtype, hipStream_t stream);

@@ -1,0 +1,133 @@
+"""GPU parity of the backward pass (gradients with respect to q, k_suf, v_suf; the prefix is a
+constant) through the C ABI against the CPU oracle's backward on the same seeded inputs.  The
+forward results the backward call consumes (out, lse) come from the HIP forward call, as they
+would in use; padded rows of every input, dout included, are NaN-poisoned."""
+import numpy as np
+import pytest
+
+from oracle import pskv_oracle as orc
+from paper_2603_13420_amd import inputs as gen
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def pk():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2603_13420_amd import binding
+    binding.load()
+    return binding
+
+
+def make_dout(inp, seed):
+    """Seeded N(0,1) incoming gradient in the workload's storage type, NaN on padded rows.
+    Returns (host array in storage form, float64 values for the oracle)."""
+    w = inp.w
+    rng = np.random.default_rng(seed)
+    a = rng.standard_normal(size=(w.B, w.S, w.Hq, w.D), dtype=np.float32)
+    a[np.arange(w.S)[None, :] >= inp.suf_len[:, None]] = np.nan
+    if w.dtype == "bf16":
+        bits = gen.f32_to_bf16_bits(a)
+        return bits, gen.bf16_bits_to_f32(bits).astype(np.float64)
+    return a, a.astype(np.float64)
+
+
+def compare_grad(got, ref, valid_rows, dtype, what):
+    """Same bars as the forward pass, applied to a gradient tensor [B,S,H,D]."""
+    assert not np.isnan(got).any(), f"{what}: NaN"
+    assert np.all(got[~valid_rows] == 0.0), f"{what}: padded rows must be exactly 0"
+    g, r = got[valid_rows], ref[valid_rows]
+    if g.size == 0:
+        return {"n": 0}
+    err = np.abs(g - r)
+    res = {"n": int(g.size), "max_abs": float(err.max())}
+    if dtype == "f32":
+        # Relative to the element, with a floor at 1e-2 of the tensor's largest magnitude.  A
+        # gradient element is a signed sum that may cancel to (nearly) zero, and the backward call
+        # consumes out and lse as fp32 numbers (unit round-off 6e-8): a perturbation of lse by
+        # 6e-8 |lse| moves every weight of the row by about 3e-7 of itself, hence the sum by about
+        # 1e-7 of the magnitude of its terms however small the sum itself comes out.
+        floor = 1e-2 * float(np.abs(r).max())
+        res["max_rel"] = float((err / np.maximum(np.abs(r), floor)).max())
+        assert res["max_rel"] <= pu.F32_REL, f"{what}: relative error {res['max_rel']:.3e}"
+    else:
+        sd = float(r.std())
+        bound = pu.BF16_REL * np.abs(r) + pu.BF16_TIGHT_STD * sd
+        res["std_ref"] = sd
+        res["tight_ratio"] = float((err / np.maximum(bound, 1e-300)).max())
+        assert res["max_abs"] <= pu.BF16_ABS * max(1.0, sd), f"{what}: max abs error {res['max_abs']:.3e}"
+        assert res["tight_ratio"] <= 1.0, f"{what}: |err| / (2e-2 std + 2^-7|ref|) = {res['tight_ratio']:.3f}"
+    return res
+
+
+def run_bwd(pk, inp, impl="auto", what=""):
+    import torch
+    w = inp.w
+    d = pu.to_device(inp)
+    print(f"[case] bwd {what or w.name} impl={impl} B={w.B} P={w.P} S={w.S} Hq={w.Hq} Hkv={w.Hkv} D={w.D} "
+          f"{w.dtype} seed={w.seed}", flush=True)
+    lse = torch.empty((w.B, w.Hq, w.S), dtype=torch.float32, device="cuda:0")
+    out = pk.pskv_attn_fwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], lse=lse,
+                           scale=inp.scale)
+    dout_host, dout64 = make_dout(inp, w.seed + 7)
+    t = torch.from_numpy(dout_host)
+    dout = (t.view(torch.bfloat16) if w.dtype == "bf16" else t).to("cuda:0")
+    nan = float("nan")
+    dq, dk, dv = (torch.full_like(d["q"], nan), torch.full_like(d["k_suf"], nan), torch.full_like(d["k_suf"], nan))
+    pk.pskv_attn_bwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], out, lse, dout,
+                     dq=dq, dk_suf=dk, dv_suf=dv, impl=impl, scale=inp.scale)
+    torch.cuda.synchronize()
+    dout64 = np.nan_to_num(dout64, nan=0.0)     # the oracle ignores padded rows; give it finite numbers there
+    P = w.P
+    kp = inp.k_pre if P > 0 else np.zeros((0, w.Hkv, w.D), dtype=inp.q.dtype)
+    vp = inp.v_pre if P > 0 else np.zeros((0, w.Hkv, w.D), dtype=inp.q.dtype)
+    rq, rk, rv = orc.attn_bwd(inp.q, inp.k_suf, inp.v_suf, kp, vp, inp.suf_len, dout64, inp.scale, w.dtype)
+    valid = np.arange(w.S)[None, :] < inp.suf_len[:, None]
+    res = {n: compare_grad(pu.out_to_f64(g), r, valid, w.dtype, f"{what or w.name} {n}")
+           for n, g, r in (("dq", dq, rq), ("dk_suf", dk, rk), ("dv_suf", dv, rv))}
+    print(f"       {res}", flush=True)
+    return res
+
+
+def test_bwd_tiny_f32(pk):
+    run_bwd(pk, gen.make_inputs(gen.WORKLOADS["tiny_f32"], pad="nan"))
+
+
+@pytest.mark.parametrize("B,P,S,lo,hi,Hq,Hkv", [
+    (5, 48, 16, 1, 16, 4, 4),       # MHA, ragged
+    (6, 256, 24, 16, 24, 8, 2),     # GQA group 4, the headline shape in small
+    (3, 0, 24, 0, 24, 4, 1),        # no prefix; one candidate may be empty
+    (3, 300, 33, 5, 33, 14, 2),     # group 7, odd sizes, long prefix
+    (2, 700, 70, 33, 70, 2, 2),     # long suffix-side segment
+])
+def test_bwd_small_shapes_bf16(pk, B, P, S, lo, hi, Hq, Hkv):
+    w = gen.custom_workload(f"bwd_{B}_{P}_{S}_{Hq}_{Hkv}", B, P, S, lo, hi, Hq, Hkv, 128, "bf16", index=800 + B + P)
+    run_bwd(pk, gen.make_inputs(w, pad="nan"))
+
+
+@pytest.mark.parametrize("D", [32, 64, 256])
+def test_bwd_other_head_dims(pk, D):
+    for dtype in ("f32", "bf16"):
+        w = gen.custom_workload(f"bwd_d{D}_{dtype}", 3, 21, 9, 0, 9, 6, 3, D, dtype, index=850 + D)
+        run_bwd(pk, gen.make_inputs(w, pad="nan"))
+
+
+def test_bwd_refuses_missing_lse_and_mfma(pk):
+    import torch
+    w = gen.custom_workload("bwd_err", 2, 16, 8, 8, 8, 2, 2, 128, "bf16", index=870)
+    inp = gen.make_inputs(w, pad="zero")
+    d = pu.to_device(inp)
+    lse = torch.empty((w.B, w.Hq, w.S), dtype=torch.float32, device="cuda:0")
+    out = pk.pskv_attn_fwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], lse=lse)
+    with pytest.raises(ValueError):
+        pk.pskv_attn_bwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], out, None, out)
+    with pytest.raises(pk.PskvError) as e:
+        pk.pskv_attn_bwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], out, lse,
+                         torch.ones_like(out), impl="mfma")
+    assert e.value.status == pk.PSKV_ERR_UNSUPPORTED
+    with pytest.raises(pk.PskvError) as e:   # an output aliasing an input
+        pk.pskv_attn_bwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], out, lse,
+                         torch.ones_like(out), dq=d["q"])
+    assert e.value.status == pk.PSKV_ERR_INVALID_ARG
