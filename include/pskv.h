@@ -205,8 +205,10 @@ pskv_status pskv_attn_fwd_multi(const pskv_multi_params *p,
  *   dk_suf, dv_suf [B,S,Hkv,D] device, written in full, laid out like k_suf; padded rows = 0
  *
  * Padded rows of dout are ignored.  Same ownership, stream and error rules as the forward call;
- * outputs must not alias inputs or one another.  p->impl: AUTO and SIMPLE select the vector-ALU
- * kernels (fp64 arithmetic for f32 tensors, fp32 for bf16); MFMA is refused in this version.
+ * outputs must not alias inputs or one another.  p->impl: SIMPLE selects the vector-ALU kernels
+ * (fp64 arithmetic for f32 tensors, fp32 for bf16); AUTO computes dq on the matrix cores when the
+ * tensors are bf16 with D == 128 (dk_suf and dv_suf, a small share of the work, stay on the
+ * vector ALU); MFMA insists on that and is refused otherwise.
  */
 pskv_status pskv_attn_bwd(const pskv_attn_params *p,
                           const void *q, const void *k_suf, const void *v_suf,

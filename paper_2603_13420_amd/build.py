@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpskv.so")
-SOURCES = ["pskv_api.cpp", "pskv_simple.hip", "pskv_stream.hip", "pskv_resident.hip", "pskv_bwd_simple.hip"]
+SOURCES = ["pskv_api.cpp", "pskv_simple.hip", "pskv_stream.hip", "pskv_resident.hip", "pskv_bwd_simple.hip", "pskv_bwd_mfma.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # Packed-fp32 VALU forms are switched off for all device code (the host pass does not know
 # the feature and says so; that warning is harmless).

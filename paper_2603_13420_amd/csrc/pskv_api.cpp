@@ -237,9 +237,10 @@ pskv_status pskv_attn_bwd(const pskv_attn_params *p, const void *q, const void *
     pskv_status s = resolve(p, 1, 0, a, use_mfma);
     if (s != PSKV_OK)
         return s;
-    if (p->impl == PSKV_IMPL_MFMA)
-        return fail(PSKV_ERR_UNSUPPORTED, "the backward pass has no MFMA path in this version");
-    if (pskv::bwd_simple_lds_bytes(a, p->dtype) > kSimpleMaxLds)
+    const bool dq_mfma = use_mfma && pskv::bwd_mfma_supported(a, p->dtype);
+    if (p->impl == PSKV_IMPL_MFMA && !dq_mfma)
+        return fail(PSKV_ERR_UNSUPPORTED, "the MFMA path of the backward pass needs dtype bf16 and D == 128");
+    if (!dq_mfma && pskv::bwd_simple_lds_bytes(a, p->dtype) > kSimpleMaxLds)
         return fail(PSKV_ERR_UNSUPPORTED, "the backward pass keeps one score row in LDS: P+S+2D=%d is too large",
                     p->P + p->S + 2 * p->D);
     if (!q || !k_suf || !v_suf || !out || !lse || !dout || !dq || !dk_suf || !dv_suf)
@@ -268,7 +269,7 @@ pskv_status pskv_attn_bwd(const pskv_attn_params *p, const void *q, const void *
     a.lse = const_cast<float *>(lse);
     g.dout = dout; g.dq = dq; g.dk = dk_suf; g.dv = dv_suf;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    hipError_t e = pskv::launch_bwd_dq_simple(g, p->dtype, stream);
+    hipError_t e = dq_mfma ? pskv::launch_bwd_dq_mfma(g, stream) : pskv::launch_bwd_dq_simple(g, p->dtype, stream);
     if (e == hipSuccess)
         e = pskv::launch_bwd_dkv_simple(g, p->dtype, stream);
     if (e != hipSuccess)

@@ -1,0 +1,274 @@
+// Matrix-core kernel for the query gradient of batched candidate-suffix attention on gfx950
+// (bf16 tensors, head dim 128, single shared prefix of any length, any suffix shape).
+//
+// For a query row with softmax weights p_j = exp(s_j - lse) over its visible rows
+// (prefix, then own suffix rows 0..i; derivative of Eq. 2, prefix K/V constant):
+//     dp_j = <dout_row, V_j>,   ds_j = p_j (dp_j - <dout_row, out_row>),   dq_row = scale * sum_j ds_j K_j.
+// Work is laid out as in the streamed forward kernels: a pass is one (KV head, group of 256
+// stacked rows r = (b*S + i)*G + g) pair, each of the 8 wavefronts of a workgroup owns one
+// 32-row block, and the prefix goes through LDS tile by tile (32 keys), double-buffered, one
+// barrier per tile, read from HBM once and used by all 256 rows.  Per tile and block, with the
+// transposed formulation of pskv_mfma.hpp (a lane owns one query column):
+//     S^T  = K Q^T        A = K fragment (row-major image),   B = Q fragment
+//     dP^T = V dO^T       A = V fragment (row-major image),   B = dO fragment
+//     dS^T = P^T o (dP^T - D)                                 vector ALU, P^T = exp2(c S^T - lse)
+//     dQ^T += K^T dS^T    A = K^T fragment (transposing image), B = dS^T packed to bf16
+// so a slot of the LDS ring holds three 8 KB images: K and V row-major, K once more in the
+// layout the transposing read wants.  The suffix rows of the block's own candidate(s) follow,
+// with K/V fragments straight from global memory and K^T through the per-wave scratch tile.
+// No running maximum is needed: lse comes from the forward pass, every weight is at most one.
+#include "pskv_mfma.hpp"
+
+namespace pskv {
+namespace {
+
+constexpr int kBwdSlotBytes = 3 * kTileBytes;
+constexpr int kBwdLdsBytes = 2 * kBwdSlotBytes + kNW * kScrBytes;
+constexpr int kBwdPassRows = kNW * kBlockRows;
+
+// Rows of a [.,.,H,D] tensor laid out like out (dout, out): lane (row c32, half h) gets
+// d = 16*ks + 8*h ..+7 for ks = 0..7, as load_q does for q.
+__device__ inline void load_o_like(const Args &a, const Ctx &X, const Row &x, const void *base, uintx4 (&dst)[8])
+{
+    const unsigned short *r = reinterpret_cast<const unsigned short *>(base) + (long long)x.rb * a.o_sb +
+                              (long long)x.ri * a.o_ss + (long long)x.rh * a.o_sh + 8 * X.h;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+        dst[ks] = ld_global16(r + 16 * ks);
+}
+
+__device__ inline float bf16_lo(unsigned w) { return __uint_as_float(w << 16); }
+__device__ inline float bf16_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
+
+// dS^T of one 32-key tile from its raw scores s and dp; element e is visible iff vis(e).
+// Returns the two B fragments (keys 0..15, 16..31) of the following product.
+template <typename VIS>
+__device__ inline void ds_tile(const floatx16 &s, const floatx16 &dp, float c, float lse2, float drow, VIS vis,
+                               bf16x8 (&pf)[2])
+{
+    float ds[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        const float p = vis(e) ? fast_exp2(__builtin_fmaf(s[e], c, -lse2)) : 0.f;
+        ds[e] = p * (dp[e] - drow);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        uintx4 w = {pack_bf16(ds[8 * j + 0], ds[8 * j + 1]), pack_bf16(ds[8 * j + 2], ds[8 * j + 3]),
+                    pack_bf16(ds[8 * j + 4], ds[8 * j + 5]), pack_bf16(ds[8 * j + 6], ds[8 * j + 7])};
+        pf[j] = as_bf16x8(w);
+    }
+}
+
+__global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
+void bwd_dq_mfma_kernel(BwdArgs g, int npasses)
+{
+    const Args &a = g.f;
+    extern __shared__ __align__(16) unsigned char smem_generic[];
+    lds_u8 *smem = (lds_u8 *)smem_generic;
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    Ctx X;
+    X.lane = tid & 63;
+    X.h = X.lane >> 5;
+    X.c32 = X.lane & 31;
+    X.Mtot = a.C * a.S * a.G;
+    X.c = a.scale * kLog2e;
+    X.k_lane = smem + X.lane * 16;                  // K row-major image of slot 0
+    X.v_lane = smem + 2 * kTileBytes + X.lane * 8;  // K transposing image of slot 0
+    X.scr = smem + 2 * kBwdSlotBytes + wave * kScrBytes;
+    X.sv_row_lo = 4 * ((X.c32 >> 4) & 1) + ((X.c32 >> 1) & 3);
+    X.sv_chunk_lo = 2 * ((X.c32 >> 3) & 1) + (X.c32 & 1);
+    lds_u8 *vk_lane = smem + kTileBytes + X.lane * 16; // V row-major image of slot 0
+    const int nblocks = (X.Mtot + kBlockRows - 1) / kBlockRows;
+    const TileSlot t = make_tile_slot(tid);
+    const int VH = a.Np * a.Hkv;
+    // the gradient goes out through the forward pass's store routine: dq is laid out like q
+    Args ad = a;
+    ad.out = g.dq;
+    ad.lse = nullptr;
+    ad.o_sb = a.q_sb;
+    ad.o_ss = a.q_ss;
+    ad.o_sh = a.q_sh;
+
+    for (int p = blockIdx.x; p < npasses; p += gridDim.x) {
+        set_vhead(a, X, p % VH);
+        const int blk_raw = (p / VH) * kNW + wave;
+        const bool active = blk_raw < nblocks;
+        const int blk = active ? blk_raw : nblocks - 1;
+        const int r0 = blk * kBlockRows;
+        const int ntiles = (X.P + kTileKeys - 1) / kTileKeys;
+        const Row row = decode_row(a, X, blk);
+        const bool rvalid = active && row.rin && (int)row.ri < clamp_len(a, row.rlen);
+        const bool work = __builtin_amdgcn_ballot_w64(rvalid) != 0;
+
+        uintx4 q[8], dof[8];
+        load_q(a, X, row, q);
+        load_o_like(a, X, row, g.dout, dof);
+        float drow = 0.f; // <dout_row, out_row>: this lane's 64 columns, then the other half-wave's
+        {
+            uintx4 of[8];
+            load_o_like(a, X, row, a.out, of);
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    drow = __builtin_fmaf(bf16_lo(dof[ks][e]), bf16_lo(of[ks][e]), drow);
+                    drow = __builtin_fmaf(bf16_hi(dof[ks][e]), bf16_hi(of[ks][e]), drow);
+                }
+            drow += __shfl_xor(drow, 32, 64);
+        }
+        const float lse2 = (row.rin ? a.lse[((long long)row.rb * a.Hq + row.rh) * a.S + row.ri] : 0.f) * kLog2e;
+
+        floatx16 o[4];
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                o[dt][e] = 0.f;
+
+        // ---- prefix part: every row sees every prefix key ----
+        if (ntiles > 0) {
+            uintx4 kk, vk, kt2;
+            auto fetch = [&](int kt) {
+                uintx4 unused;
+                load_tile_chunks(a, X, t, kt, kk, unused);   // K chunk for the row-major image; (V chunk of the transposing slot unused)
+                // V chunk for the row-major image and K chunk for the transposing image
+                const int last = X.P > 0 ? X.P - 1 : 0;
+                const int kkey = kt * kTileKeys + t.k_row, vkey = kt * kTileKeys + t.v_row;
+                vk = ld_global16(X.vpg + (long long)(kkey < X.P ? kkey : last) * a.kp_sp + t.k_chunk * 8);
+                kt2 = ld_global16(X.kpg + (long long)(vkey < X.P ? vkey : last) * a.kp_sp + t.v_chunk * 8);
+            };
+            auto put = [&](int kt, int slot) {
+                const int kkey = kt * kTileKeys + t.k_row, vkey = kt * kTileKeys + t.v_row;
+                lds_u8 *s0 = smem + slot * kBwdSlotBytes + tid * 16;
+                *(lds_u128 *)s0 = kkey < X.P ? kk : uintx4{0, 0, 0, 0};
+                *(lds_u128 *)(s0 + kTileBytes) = kkey < X.P ? vk : uintx4{0, 0, 0, 0};
+                *(lds_u128 *)(s0 + 2 * kTileBytes) = vkey < X.P ? kt2 : uintx4{0, 0, 0, 0};
+            };
+            fetch(0);
+            __syncthreads(); // whatever the slots held has been used by every wavefront
+            put(0, 0);
+            __syncthreads();
+            for (int kt = 0; kt < ntiles; ++kt) {
+                fetch(kt + 1 < ntiles ? kt + 1 : kt);
+                if (work) {
+                    const int so = (kt & 1) * kBwdSlotBytes;
+                    floatx16 s, dp;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        s[e] = 0.f;
+                        dp[e] = 0.f;
+                    }
+#pragma unroll
+                    for (int ks = 0; ks < 8; ++ks) {
+                        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*(lds_u128 *)(X.k_lane + so + ks * 1024)),
+                                                                    as_bf16x8(q[ks]), s, 0, 0, 0);
+                        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*(lds_u128 *)(vk_lane + so + ks * 1024)),
+                                                                     as_bf16x8(dof[ks]), dp, 0, 0, 0);
+                    }
+                    const int nv = X.P - kt * kTileKeys - 4 * X.h; // element e holds key 8*(e/4) + e%4 + 4*h of the tile
+                    bf16x8 pf[2];
+                    ds_tile(s, dp, X.c, lse2, drow, [&](int e) { return 8 * (e >> 2) + (e & 3) < nv; }, pf);
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int dt = 0; dt < 4; ++dt)
+                            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_fragment(X.v_lane + so, dt, j), pf[j], o[dt], 0,
+                                                                            0, 0);
+                }
+                if (kt + 1 < ntiles)
+                    put(kt + 1, (kt + 1) & 1);
+                __syncthreads();
+            }
+        }
+
+        // ---- suffix part: (candidate, 32-key step) pairs, wave-uniform ----
+        if (work) {
+            Ctx Xs = X; // K and V of the suffix trade places: V in row-major fragments, K through the scratch tile
+            Xs.ksg = X.vsg;
+            Xs.vsg = X.ksg;
+            const int last_row = r0 + kBlockRows - 1 < X.Mtot ? r0 + kBlockRows - 1 : X.Mtot - 1;
+            const int tok_first = fdiv(r0, a.div_g), tok_last = fdiv(last_row, a.div_g);
+            const int bl_last = fdiv(tok_last, a.div_s);
+            for (int bl = fdiv(tok_first, a.div_s); bl <= bl_last; ++bl) {
+                const int b = X.cand0 + bl;
+                const int len = len_uniform(a, b);
+                const int i_lo = tok_first - bl * a.S > 0 ? tok_first - bl * a.S : 0;
+                const int i_hi = tok_last - bl * a.S < a.S - 1 ? tok_last - bl * a.S : a.S - 1;
+                const int kmax = i_hi < len - 1 ? i_hi : len - 1;
+                if (i_lo >= len)
+                    continue;
+                for (int k0 = 0; k0 <= kmax; k0 += kTileKeys) {
+                    floatx16 s, dp;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        s[e] = 0.f;
+                        dp[e] = 0.f;
+                    }
+                    {
+                        uintx4 kf[8];
+                        load_suffix_k(a, X, b, k0, kmax, kf);
+#pragma unroll
+                        for (int ks = 0; ks < 8; ++ks)
+                            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[ks]), as_bf16x8(q[ks]), s, 0, 0, 0);
+                    }
+                    {
+                        uintx4 vf[8];
+                        load_suffix_k(a, Xs, b, k0, kmax, vf); // V rows as row-major fragments
+#pragma unroll
+                        for (int ks = 0; ks < 8; ++ks)
+                            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vf[ks]), as_bf16x8(dof[ks]), dp, 0, 0, 0);
+                    }
+                    uintx4 ktf[2][4];
+                    load_suffix_v(a, Xs, b, k0, kmax, ktf); // K rows in scratch-image order
+                    // the row sees keys 0..ri of its own candidate; element e holds key k0 + 8*(e/4) + e%4 + 4*h
+                    const int lim = ((int)row.rb == b ? (int)row.ri : -1) - k0 - 4 * X.h;
+                    bf16x8 pf[2];
+                    ds_tile(s, dp, X.c, lse2, drow, [&](int e) { return 8 * (e >> 2) + (e & 3) <= lim; }, pf);
+                    pv_from_scratch(X, ktf[0], pf[0], o);
+                    pv_from_scratch(X, ktf[1], pf[1], o);
+                }
+            }
+        }
+        if (active) {
+            if (work) // store_block divides by the sum of both half-waves' l: 1/(2 * 0.5/scale) = scale
+                store_block(ad, X, r0, row, rvalid, 0.f, 0.5f / a.scale, o);
+            else
+                store_zero_block(ad, X, row);
+        }
+    }
+}
+
+} // namespace
+
+bool bwd_mfma_supported(const Args &a, int dtype)
+{
+    return mfma_supported(a, dtype) && a.Np == 1 && a.plen == nullptr;
+}
+
+hipError_t launch_bwd_dq_mfma(const BwdArgs &g, hipStream_t stream)
+{
+    static int num_cu = 0;
+    if (num_cu == 0) {
+        int dev = 0, n = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess)
+            e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(bwd_dq_mfma_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kBwdLdsBytes);
+        if (e != hipSuccess)
+            return e;
+        num_cu = n > 0 ? n : 256;
+    }
+    const Args &a = g.f;
+    const long long rows = (long long)a.C * a.S * a.G;
+    const long long npasses = ((rows + kBwdPassRows - 1) / kBwdPassRows) * a.Np * a.Hkv;
+    // two workgroups fit a compute unit's LDS; registers allow one, so one per compute unit
+    const unsigned grid = (unsigned)(npasses < num_cu ? npasses : num_cu);
+    hipLaunchKernelGGL(bwd_dq_mfma_kernel, dim3(grid), dim3(kNW * 64), kBwdLdsBytes, stream, g, (int)npasses);
+    return hipGetLastError();
+}
+
+} // namespace pskv

@@ -95,6 +95,7 @@ def test_bwd_tiny_f32(pk):
     run_bwd(pk, gen.make_inputs(gen.WORKLOADS["tiny_f32"], pad="nan"))
 
 
+@pytest.mark.parametrize("impl", ["simple", "mfma"])
 @pytest.mark.parametrize("B,P,S,lo,hi,Hq,Hkv", [
     (5, 48, 16, 1, 16, 4, 4),       # MHA, ragged
     (6, 256, 24, 16, 24, 8, 2),     # GQA group 4, the headline shape in small
@@ -102,9 +103,36 @@ def test_bwd_tiny_f32(pk):
     (3, 300, 33, 5, 33, 14, 2),     # group 7, odd sizes, long prefix
     (2, 700, 70, 33, 70, 2, 2),     # long suffix-side segment
 ])
-def test_bwd_small_shapes_bf16(pk, B, P, S, lo, hi, Hq, Hkv):
+def test_bwd_small_shapes_bf16(pk, impl, B, P, S, lo, hi, Hq, Hkv):
     w = gen.custom_workload(f"bwd_{B}_{P}_{S}_{Hq}_{Hkv}", B, P, S, lo, hi, Hq, Hkv, 128, "bf16", index=800 + B + P)
-    run_bwd(pk, gen.make_inputs(w, pad="nan"))
+    run_bwd(pk, gen.make_inputs(w, pad="nan"), impl=impl)
+
+
+def test_bwd_headline_shape_sampled(pk):
+    """The 8B-class GQA shape at full size through the matrix-core path; the oracle recomputes a
+    sample of candidates (a candidate's gradients depend only on the prefix and on itself)."""
+    import torch
+    inp = gen.make_inputs(gen.WORKLOADS["gqa8b_bf16"], pad="nan", workers=16)
+    w = inp.w
+    d = pu.to_device(inp)
+    lse = torch.empty((w.B, w.Hq, w.S), dtype=torch.float32, device="cuda:0")
+    out = pk.pskv_attn_fwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], lse=lse, scale=inp.scale)
+    dout_host, dout64 = make_dout(inp, w.seed + 7)
+    dout = torch.from_numpy(dout_host).view(torch.bfloat16).to("cuda:0")
+    dq, dk, dv = pk.pskv_attn_bwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], out, lse, dout,
+                                  scale=inp.scale)
+    torch.cuda.synchronize()
+    cand = np.array(sorted({0, 1, w.B // 2, w.B - 1, int(np.argmin(inp.suf_len)), int(np.argmax(inp.suf_len))}))
+    sub = inp.take(cand)
+    rq, rk, rv = orc.attn_bwd(sub.q, sub.k_suf, sub.v_suf, sub.k_pre, sub.v_pre, sub.suf_len,
+                              np.nan_to_num(dout64[cand], nan=0.0), sub.scale, w.dtype)
+    sel = torch.from_numpy(cand).to("cuda:0")
+    valid = np.arange(w.S)[None, :] < sub.suf_len[:, None]
+    for n, gt, r in (("dq", dq, rq), ("dk_suf", dk, rk), ("dv_suf", dv, rv)):
+        print("      ", n, compare_grad(pu.out_to_f64(gt[sel]), r, valid, "bf16", f"gqa8b {n}"), flush=True)
+    pad = ~(torch.arange(w.S, device="cuda:0")[None, :] < d["suf_len"][:, None])
+    assert (dq[pad] == 0).all() and (dk[pad] == 0).all() and (dv[pad] == 0).all()
+    assert torch.isfinite(dq.float()).all() and torch.isfinite(dk.float()).all() and torch.isfinite(dv.float()).all()
 
 
 @pytest.mark.parametrize("D", [32, 64, 256])
@@ -114,7 +142,7 @@ def test_bwd_other_head_dims(pk, D):
         run_bwd(pk, gen.make_inputs(w, pad="nan"))
 
 
-def test_bwd_refuses_missing_lse_and_mfma(pk):
+def test_bwd_refuses_missing_lse_wrong_path_and_aliases(pk):
     import torch
     w = gen.custom_workload("bwd_err", 2, 16, 8, 8, 8, 2, 2, 128, "bf16", index=870)
     inp = gen.make_inputs(w, pad="zero")
@@ -123,9 +151,13 @@ def test_bwd_refuses_missing_lse_and_mfma(pk):
     out = pk.pskv_attn_fwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], lse=lse)
     with pytest.raises(ValueError):
         pk.pskv_attn_bwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], out, None, out)
-    with pytest.raises(pk.PskvError) as e:
-        pk.pskv_attn_bwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], out, lse,
-                         torch.ones_like(out), impl="mfma")
+    w32 = gen.custom_workload("bwd_err32", 2, 16, 8, 8, 8, 2, 2, 64, "f32", index=871)
+    d32 = pu.to_device(gen.make_inputs(w32, pad="zero"))
+    lse32 = torch.empty((2, 2, 8), dtype=torch.float32, device="cuda:0")
+    out32 = pk.pskv_attn_fwd(d32["q"], d32["k_suf"], d32["v_suf"], d32["k_pre"], d32["v_pre"], d32["suf_len"], lse=lse32)
+    with pytest.raises(pk.PskvError) as e:   # the matrix-core path is for bf16, D == 128
+        pk.pskv_attn_bwd(d32["q"], d32["k_suf"], d32["v_suf"], d32["k_pre"], d32["v_pre"], d32["suf_len"], out32, lse32,
+                         torch.ones_like(out32), impl="mfma")
     assert e.value.status == pk.PSKV_ERR_UNSUPPORTED
     with pytest.raises(pk.PskvError) as e:   # an output aliasing an input
         pk.pskv_attn_bwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], out, lse,
