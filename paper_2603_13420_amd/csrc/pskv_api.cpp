@@ -243,6 +243,9 @@ pskv_status pskv_attn_bwd(const pskv_attn_params *p, const void *q, const void *
     if (!dq_mfma && pskv::bwd_simple_lds_bytes(a, p->dtype) > kSimpleMaxLds)
         return fail(PSKV_ERR_UNSUPPORTED, "the backward pass keeps one score row in LDS: P+S+2D=%d is too large",
                     p->P + p->S + 2 * p->D);
+    if (!dq_mfma && pskv::bwd_dkv_lds_bytes(a, p->dtype) > kSimpleMaxLds)
+        return fail(PSKV_ERR_UNSUPPORTED, "the dk/dv kernel keeps one value per query row of a group in LDS: G*S=%d is too large",
+                    a.G * p->S);
     if (!q || !k_suf || !v_suf || !out || !lse || !dout || !dq || !dk_suf || !dv_suf)
         return fail(PSKV_ERR_INVALID_ARG, "q, k_suf, v_suf, out, lse, dout, dq, dk_suf and dv_suf must not be NULL");
     if (a.P > 0 && (!k_pre || !v_pre))
@@ -271,7 +274,7 @@ pskv_status pskv_attn_bwd(const pskv_attn_params *p, const void *q, const void *
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipError_t e = dq_mfma ? pskv::launch_bwd_dq_mfma(g, stream) : pskv::launch_bwd_dq_simple(g, p->dtype, stream);
     if (e == hipSuccess)
-        e = pskv::launch_bwd_dkv_simple(g, p->dtype, stream);
+        e = dq_mfma ? pskv::launch_bwd_dkv_mfma(g, stream) : pskv::launch_bwd_dkv_simple(g, p->dtype, stream);
     if (e != hipSuccess)
         return fail(PSKV_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
     g_err[0] = '\0';

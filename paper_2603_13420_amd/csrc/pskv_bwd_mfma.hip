@@ -22,6 +22,8 @@
 namespace pskv {
 namespace {
 
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
 constexpr int kBwdSlotBytes = 3 * kTileBytes;
 constexpr int kBwdLdsBytes = 2 * kBwdSlotBytes + kNW * kScrBytes;
 constexpr int kBwdPassRows = kNW * kBlockRows;
@@ -240,11 +242,248 @@ void bwd_dq_mfma_kernel(BwdArgs g, int npasses)
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// dk_suf, dv_suf on the matrix cores.  One wavefront per (candidate, KV head, tile of 32 suffix
+// keys, half DH of the 128 output columns: the accumulators of both halves would not fit the
+// register file); it walks over the candidate's 32-row blocks of stacked query rows (i, g) that can see
+// the tile and accumulates, in the non-transposed formulation (a lane owns one key column):
+//     S   = Q K^T          A = Q fragment,   B = K fragment (both straight from global memory)
+//     dP  = dO V^T         A = dO fragment,  B = V fragment
+//     P   = exp2(c S - lse),  dS = P o (dP - D)      per element: row quantities come through LDS
+//     dV^T += dO^T P       A = dO^T through the scratch tile,  B = P packed to bf16
+//     dK^T += Q^T dS       A = Q^T through the scratch tile,   B = dS packed to bf16
+// The accumulators of S hold, for lane half h, rows 8*kk + 4*h + t of the block in element
+// 4*kk + t: exactly the order in which the scratch image hands out the rows of dO and Q, so P
+// and dS go from the first products to the second ones through registers only.
+// ------------------------------------------------------------------------------------------
+constexpr int kDkvWaves = 4;
+constexpr int kDkvAux = 512; // per wavefront: lse, <dout,out> and suffix position of the block's 32 rows
+constexpr int kDkvLdsBytes = kDkvWaves * (kScrBytes + kDkvAux);
+
+// O^T-style accumulation of two 32-column groups (dt = 2*DH, 2*DH+1) for one 16-row step whose
+// rows are in registers in scratch-image order: through the scratch tile (cf. pv_from_scratch).
+template <int DH>
+__device__ inline void pv_half_from_scratch(const Ctx &X, const uintx4 (&vstep)[2], bf16x8 pfj, floatx16 (&o)[2])
+{
+#pragma unroll
+    for (int i2 = 0; i2 < 2; ++i2)
+        *(lds_u128 *)(X.scr + (2 * DH + i2) * 1024 + X.lane * 16) = vstep[i2];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    bf16x8 va[2];
+#pragma unroll
+    for (int i2 = 0; i2 < 2; ++i2) {
+        const int dt = 2 * DH + i2;
+        short4v lo = lds_read_tr(X.scr + X.lane * 8 + (dt * 2 + 0) * 512);
+        short4v hi = lds_read_tr(X.scr + X.lane * 8 + (dt * 2 + 1) * 512);
+        short8v v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        __builtin_memcpy(&va[i2], &v8, 16);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int i2 = 0; i2 < 2; ++i2)
+        o[i2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i2], pfj, o[i2], 0, 0, 0);
+}
+
+template <int DH>
+__device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, lds_u8 *smem, int tid, int wave, int unit,
+                                                            int nkt)
+{
+    const Args &a = g.f;
+    const int kt = unit % nkt, bk = unit / nkt;
+    const int k = bk % a.Hkv, b = bk / a.Hkv;
+    const int k0 = kt * kTileKeys;
+
+    Ctx X;
+    X.lane = tid & 63;
+    X.h = X.lane >> 5;
+    X.c32 = X.lane & 31;
+    X.Mtot = a.S * a.G; // rows of this candidate
+    X.c = a.scale * kLog2e;
+    X.scr = smem + wave * (kScrBytes + kDkvAux);
+    X.sv_row_lo = 4 * ((X.c32 >> 4) & 1) + ((X.c32 >> 1) & 3);
+    X.sv_chunk_lo = 2 * ((X.c32 >> 3) & 1) + (X.c32 & 1);
+    X.head = k;
+    X.cand0 = 0;
+    X.P = 0;
+    X.ksg = reinterpret_cast<const unsigned short *>(a.ks) + (long long)k * a.ks_sh;
+    X.vsg = reinterpret_cast<const unsigned short *>(a.vs) + (long long)k * a.ks_sh;
+    Ctx Xs = X; // V rows as row-major fragments
+    Xs.ksg = X.vsg;
+    Xs.vsg = X.ksg;
+    typedef __attribute__((address_space(3))) float lds_f32;
+    typedef __attribute__((address_space(3))) floatx4 lds_f32x4;
+    lds_f32 *aux_lse = (lds_f32 *)(X.scr + kScrBytes);
+    lds_f32 *aux_drow = aux_lse + 32;
+    lds_f32 *aux_i = aux_drow + 32; // suffix position of the row as a float, -1 for a row that does not count
+
+    const int len = len_uniform(a, b);
+    // this lane's key and where its gradients go
+    const int key = k0 + X.c32;
+    unsigned short *dst_k[4], *dst_v[4];
+    bool dst_ok[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int jr = k0 + 8 * u + (X.lane >> 3);
+        dst_ok[u] = jr < a.S;
+        const long long off = (long long)b * a.ks_sb + (long long)(dst_ok[u] ? jr : 0) * a.ks_ss + (long long)k * a.ks_sh +
+                              8 * (X.lane & 7);
+        dst_k[u] = reinterpret_cast<unsigned short *>(g.dk) + off;
+        dst_v[u] = reinterpret_cast<unsigned short *>(g.dv) + off;
+    }
+    floatx16 dk[2], dv[2]; // output columns 64*DH .. 64*DH+63
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            dk[dt][e] = 0.f;
+            dv[dt][e] = 0.f;
+        }
+
+    if (k0 < len) {
+        const int kmax = len - 1;
+        const unsigned short *qb = reinterpret_cast<const unsigned short *>(a.q) + (long long)b * a.q_sb + (long long)k * a.G * a.q_sh;
+        const long long ob = (long long)b * a.o_sb + (long long)k * a.G * a.o_sh;
+        const unsigned short *dob = reinterpret_cast<const unsigned short *>(g.dout) + ob;
+        const unsigned short *outb = reinterpret_cast<const unsigned short *>(a.out) + ob;
+        const int nrows = len * a.G; // rows (i, g) with i < len, in stacked order i*G + g
+        // the first block that holds a row with i >= k0
+        for (int rl0 = (k0 * a.G) / kBlockRows * kBlockRows; rl0 < nrows; rl0 += kBlockRows) {
+            // this lane's row of the block, clamped into the candidate
+            const int rl = rl0 + X.c32 < nrows ? rl0 + X.c32 : nrows - 1;
+            const bool rvalid = rl0 + X.c32 < nrows;
+            const int ri = (int)fdiv((unsigned)rl, a.div_g), gq = rl - ri * a.G;
+            const long long qoff = (long long)ri * a.q_ss + (long long)gq * a.q_sh + 8 * X.h;
+            const long long ooff = (long long)ri * a.o_ss + (long long)gq * a.o_sh + 8 * X.h;
+
+            floatx16 s, dp;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                s[e] = 0.f;
+                dp[e] = 0.f;
+            }
+            {
+                uintx4 qf[8], kf[8];
+                load_suffix_k(a, X, b, k0, kmax, kf);
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks)
+                    qf[ks] = ld_global16(qb + qoff + 16 * ks);
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks)
+                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qf[ks]), as_bf16x8(kf[ks]), s, 0, 0, 0);
+            }
+            float drow = 0.f;
+            {
+                uintx4 dof[8], vf[8];
+                load_suffix_k(a, Xs, b, k0, kmax, vf);
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks)
+                    dof[ks] = ld_global16(dob + ooff + 16 * ks);
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks)
+                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(dof[ks]), as_bf16x8(vf[ks]), dp, 0, 0, 0);
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) {
+                    const uintx4 of = ld_global16(outb + ooff + 16 * ks);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        drow = __builtin_fmaf(bf16_lo(dof[ks][e]), bf16_lo(of[e]), drow);
+                        drow = __builtin_fmaf(bf16_hi(dof[ks][e]), bf16_hi(of[e]), drow);
+                    }
+                }
+                drow += __shfl_xor(drow, 32, 64);
+            }
+            // row quantities to LDS, then each lane fetches those of the 16 rows its elements belong to
+            if (X.h == 0) {
+                aux_lse[X.c32] = a.lse[((long long)b * a.Hq + k * a.G + gq) * a.S + ri] * kLog2e;
+                aux_drow[X.c32] = drow;
+                aux_i[X.c32] = rvalid ? (float)ri : -1.f;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            float p[16], ds[16];
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const floatx4 l4 = *(lds_f32x4 *)(aux_lse + 8 * kk + 4 * X.h);
+                const floatx4 d4 = *(lds_f32x4 *)(aux_drow + 8 * kk + 4 * X.h);
+                const floatx4 i4 = *(lds_f32x4 *)(aux_i + 8 * kk + 4 * X.h);
+#pragma unroll
+                for (int t2 = 0; t2 < 4; ++t2) {
+                    const int e = 4 * kk + t2;
+                    // the row sees suffix key `key` iff key <= its position (and the key exists)
+                    const bool vis = (float)key <= i4[t2] && key < len;
+                    p[e] = vis ? fast_exp2(__builtin_fmaf(s[e], X.c, -l4[t2])) : 0.f;
+                    ds[e] = p[e] * (dp[e] - d4[t2]);
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            bf16x8 pfp[2], pfs[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                pfp[j] = as_bf16x8(uintx4{pack_bf16(p[8 * j + 0], p[8 * j + 1]), pack_bf16(p[8 * j + 2], p[8 * j + 3]),
+                                          pack_bf16(p[8 * j + 4], p[8 * j + 5]), pack_bf16(p[8 * j + 6], p[8 * j + 7])});
+                pfs[j] = as_bf16x8(uintx4{pack_bf16(ds[8 * j + 0], ds[8 * j + 1]), pack_bf16(ds[8 * j + 2], ds[8 * j + 3]),
+                                          pack_bf16(ds[8 * j + 4], ds[8 * j + 5]), pack_bf16(ds[8 * j + 6], ds[8 * j + 7])});
+            }
+            // dO^T and Q^T of the block through the scratch tile, 16 rows at a time
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                uintx4 dst2[2], qst2[2];
+#pragma unroll
+                for (int i2 = 0; i2 < 2; ++i2) {
+                    const int frag = 2 * (2 * DH + i2) + X.h; // fragment (dt = frag >> 1, u = frag & 1)
+                    int rb2 = rl0 + 16 * j + 8 * (frag & 1) + X.sv_row_lo;
+                    rb2 = rb2 < nrows ? rb2 : nrows - 1;
+                    const int ir = (int)fdiv((unsigned)rb2, a.div_g), g2 = rb2 - ir * a.G;
+                    const int ch = (4 * (frag >> 1) + X.sv_chunk_lo) * 8;
+                    dst2[i2] = ld_global16(dob + (long long)ir * a.o_ss + (long long)g2 * a.o_sh + ch);
+                    qst2[i2] = ld_global16(qb + (long long)ir * a.q_ss + (long long)g2 * a.q_sh + ch);
+                }
+                pv_half_from_scratch<DH>(X, dst2, pfp[j], dv);
+                pv_half_from_scratch<DH>(X, qst2, pfs[j], dk);
+            }
+        }
+    }
+    const bool kvalid = key < len;
+    // the store routine addresses accumulators by column group: hand it this half in its place
+    const floatx16 dk4[4] = {dk[0], dk[1], dk[0], dk[1]}, dv4[4] = {dv[0], dv[1], dv[0], dv[1]};
+    store_rows<DH, DH>(X, dst_k, dst_ok, kvalid, a.scale, dk4);
+    store_rows<DH, DH>(X, dst_v, dst_ok, kvalid, 1.0f, dv4);
+}
+
+__global__ __attribute__((amdgpu_flat_work_group_size(256, 256), amdgpu_waves_per_eu(2, 2)))
+void bwd_dkv_mfma_kernel(BwdArgs g, int nunits, int nkt)
+{
+    extern __shared__ __align__(16) unsigned char smem_generic[];
+    lds_u8 *smem = (lds_u8 *)smem_generic;
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int unit2 = blockIdx.x * kDkvWaves + wave; // (unit, half of the output columns)
+    if (unit2 >= 2 * nunits) // no workgroup barrier anywhere in this kernel
+        return;
+    if (unit2 & 1)
+        bwd_dkv_unit<1>(g, smem, tid, wave, unit2 >> 1, nkt);
+    else
+        bwd_dkv_unit<0>(g, smem, tid, wave, unit2 >> 1, nkt);
+}
+
 } // namespace
 
 bool bwd_mfma_supported(const Args &a, int dtype)
 {
     return mfma_supported(a, dtype) && a.Np == 1 && a.plen == nullptr;
+}
+
+hipError_t launch_bwd_dkv_mfma(const BwdArgs &g, hipStream_t stream)
+{
+    const Args &a = g.f;
+    const int nkt = (a.S + kTileKeys - 1) / kTileKeys;
+    const long long nunits = (long long)a.B * a.Hkv * nkt;
+    const unsigned grid = (unsigned)((2 * nunits + kDkvWaves - 1) / kDkvWaves);
+    hipLaunchKernelGGL(bwd_dkv_mfma_kernel, dim3(grid), dim3(kDkvWaves * 64), kDkvLdsBytes, stream, g, (int)nunits, nkt);
+    return hipGetLastError();
 }
 
 hipError_t launch_bwd_dq_mfma(const BwdArgs &g, hipStream_t stream)

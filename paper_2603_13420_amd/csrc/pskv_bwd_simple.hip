@@ -9,8 +9,9 @@
 //     dq_row = scale * sum_j ds_j K_j,  dK_j = scale * sum_rows ds_j q_row,  dV_j = sum_rows p_j dout_row.
 //   dq kernel:  one wavefront per query row (b,i,h): a sweep with one visible key per lane for
 //               ds_j, then one output column per lane for the sum over keys.
-//   dkv kernel: one wavefront per suffix key row (b,j,kv head): it visits the query rows i >= j
-//               of the G query heads that share the KV head; each lane owns output columns.
+//   dkv kernel: one wavefront per suffix key row (b,j,kv head): the query rows i >= j of the G
+//               query heads that share the KV head, one per lane for ds and p, then one output
+//               column per lane for the sums over those rows.
 // The forward pass's lse and out are taken as given (out only through <dout_row, out_row>).
 // Arithmetic: fp64 when the tensors are f32, fp32 when they are bf16; any head dimension up
 // to 256 and any GQA group size.
@@ -109,10 +110,40 @@ __global__ __launch_bounds__(64) void bwd_dq_kernel(BwdArgs g)
     }
 }
 
+// 16 bytes of a row as numbers: 8 bf16 or 4 f32 elements.
+__device__ inline int load_vec(const unsigned short *p, float (&v)[8])
+{
+    const uint4 w = *reinterpret_cast<const uint4 *>(p);
+    const unsigned u[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        v[2 * e] = __uint_as_float(u[e] << 16);
+        v[2 * e + 1] = __uint_as_float(u[e] & 0xffff0000u);
+    }
+    return 8;
+}
+__device__ inline int load_vec(const float *p, float (&v)[8])
+{
+    const float4 w = *reinterpret_cast<const float4 *>(p);
+    v[0] = w.x; v[1] = w.y; v[2] = w.z; v[3] = w.w;
+    v[4] = v[5] = v[6] = v[7] = 0.f;
+    return 4;
+}
+
+// dk_suf, dv_suf of one suffix key row (b, j, KV head).  The query rows that see the key are
+// the pairs (query head of the group, i >= j); first one lane per pair computes that row's
+// ds and p (three dot products over the head dimension with 16-byte loads, the key's K and V
+// rows broadcast from LDS), then one lane per output column sums over the pairs.
 template <typename T, typename C>
 __global__ __launch_bounds__(64) void bwd_dkv_kernel(BwdArgs g)
 {
     const Args &a = g.f;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    C *kj = reinterpret_cast<C *>(smem_raw); // [D]
+    C *vj = kj + a.D;                        // [D]
+    C *dss = vj + a.D;                       // [G*S]  scale * ds of each pair
+    C *ps = dss + a.G * a.S;                 // [G*S]  p of each pair
+
     const int lane = threadIdx.x;
     const long long row = blockIdx.x; // (b*S + j)*Hkv + k
     const int k = (int)(row % a.Hkv);
@@ -124,59 +155,54 @@ __global__ __launch_bounds__(64) void bwd_dkv_kernel(BwdArgs g)
     len = len < 0 ? 0 : (len > a.S ? a.S : len);
     T *dk = reinterpret_cast<T *>(g.dk) + b * a.ks_sb + j * a.ks_ss + k * a.ks_sh;
     T *dv = reinterpret_cast<T *>(g.dv) + b * a.ks_sb + j * a.ks_ss + k * a.ks_sh;
-    constexpr int U = 4; // output columns per lane: D <= 256
-    C kj[U], vj[U], dka[U], dva[U];
+    if (j >= len) { // padded suffix row: no gradient
+        for (int d = lane; d < a.D; d += 64) {
+            store_from(dk + d, (C)0);
+            store_from(dv + d, (C)0);
+        }
+        return;
+    }
     const T *kr = reinterpret_cast<const T *>(a.ks) + b * a.ks_sb + j * a.ks_ss + k * a.ks_sh;
     const T *vr = reinterpret_cast<const T *>(a.vs) + b * a.ks_sb + j * a.ks_ss + k * a.ks_sh;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int d = lane + 64 * u;
-        const bool in = d < a.D && j < len;
-        kj[u] = in ? (C)load_as_float(kr + d) : (C)0;
-        vj[u] = in ? (C)load_as_float(vr + d) : (C)0;
-        dka[u] = 0;
-        dva[u] = 0;
+    for (int d = lane; d < a.D; d += 64) {
+        kj[d] = (C)load_as_float(kr + d);
+        vj[d] = (C)load_as_float(vr + d);
     }
-    if (j < len) {
-        for (int gq = 0; gq < a.G; ++gq) {
-            const int h = k * a.G + gq;
-            for (int i = j; i < len; ++i) { // the query rows that see suffix key j
-                const T *q = reinterpret_cast<const T *>(a.q) + b * a.q_sb + i * a.q_ss + h * a.q_sh;
-                const T *o = reinterpret_cast<const T *>(a.out) + b * a.o_sb + i * a.o_ss + h * a.o_sh;
-                const T *dor = reinterpret_cast<const T *>(g.dout) + b * a.o_sb + i * a.o_ss + h * a.o_sh;
-                C qv[U], dov[U];
-                C s = 0, dp = 0, drow = 0;
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int d = lane + 64 * u;
-                    const bool in = d < a.D;
-                    qv[u] = in ? (C)load_as_float(q + d) : (C)0;
-                    dov[u] = in ? (C)load_as_float(dor + d) : (C)0;
-                    const C ov = in ? (C)load_as_float(o + d) : (C)0;
-                    s += qv[u] * kj[u];
-                    dp += dov[u] * vj[u];
-                    drow += dov[u] * ov;
-                }
-                s = wave_sum(s);
-                dp = wave_sum(dp);
-                drow = wave_sum(drow);
-                const C p = exp_c(s * (C)a.scale - (C)a.lse[((long long)b * a.Hq + h) * a.S + i]);
-                const C ds = p * (dp - drow) * (C)a.scale;
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    dka[u] += ds * qv[u];
-                    dva[u] += p * dov[u];
-                }
+    __syncthreads();
+    const int nrow = len - j;         // query rows i = j .. len-1 see suffix key j
+    const int npairs = a.G * nrow;    // for each of the G query heads of the group
+    for (int pr = lane; pr < npairs; pr += 64) {
+        const int gq = pr / nrow, i = j + pr - gq * nrow, h = k * a.G + gq;
+        const T *q = reinterpret_cast<const T *>(a.q) + b * a.q_sb + i * a.q_ss + h * a.q_sh;
+        const T *o = reinterpret_cast<const T *>(a.out) + b * a.o_sb + i * a.o_ss + h * a.o_sh;
+        const T *dor = reinterpret_cast<const T *>(g.dout) + b * a.o_sb + i * a.o_ss + h * a.o_sh;
+        C s = 0, dp = 0, drow = 0;
+        for (int d = 0; d < a.D;) {
+            float qv[8], dov[8], ov[8];
+            const int n = load_vec(q + d, qv);
+            load_vec(dor + d, dov);
+            load_vec(o + d, ov);
+            for (int e = 0; e < n; ++e) {
+                s += (C)qv[e] * kj[d + e];
+                dp += (C)dov[e] * vj[d + e];
+                drow += (C)dov[e] * (C)ov[e];
             }
+            d += n;
         }
+        const C p = exp_c(s * (C)a.scale - (C)a.lse[((long long)b * a.Hq + h) * a.S + i]);
+        dss[pr] = p * (dp - drow) * (C)a.scale;
+        ps[pr] = p;
     }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int d = lane + 64 * u;
-        if (d < a.D) {
-            store_from(dk + d, dka[u]);
-            store_from(dv + d, dva[u]);
+    __syncthreads();
+    for (int d = lane; d < a.D; d += 64) {
+        C dka = 0, dva = 0;
+        for (int pr = 0; pr < npairs; ++pr) {
+            const int gq = pr / nrow, i = j + pr - gq * nrow, h = k * a.G + gq;
+            dka += dss[pr] * (C)load_as_float(reinterpret_cast<const T *>(a.q) + b * a.q_sb + i * a.q_ss + h * a.q_sh + d);
+            dva += ps[pr] * (C)load_as_float(reinterpret_cast<const T *>(g.dout) + b * a.o_sb + i * a.o_ss + h * a.o_sh + d);
         }
+        store_from(dk + d, dka);
+        store_from(dv + d, dva);
     }
 }
 
@@ -186,6 +212,12 @@ size_t bwd_simple_lds_bytes(const Args &a, int dtype)
 {
     const size_t c = dtype == 0 ? sizeof(double) : sizeof(float);
     return c * (2 * (size_t)a.D + (size_t)a.P + (size_t)a.S);
+}
+
+size_t bwd_dkv_lds_bytes(const Args &a, int dtype)
+{
+    const size_t c = dtype == 0 ? sizeof(double) : sizeof(float);
+    return c * (2 * (size_t)a.D + 2 * (size_t)a.G * a.S);
 }
 
 hipError_t launch_bwd_dq_simple(const BwdArgs &g, int dtype, hipStream_t stream)
@@ -204,10 +236,11 @@ hipError_t launch_bwd_dkv_simple(const BwdArgs &g, int dtype, hipStream_t stream
 {
     const Args &a = g.f;
     const long long rows = (long long)a.B * a.S * a.Hkv;
+    const size_t lds = bwd_dkv_lds_bytes(a, dtype);
     if (dtype == 0)
-        hipLaunchKernelGGL((bwd_dkv_kernel<float, double>), dim3((unsigned)rows), dim3(64), 0, stream, g);
+        hipLaunchKernelGGL((bwd_dkv_kernel<float, double>), dim3((unsigned)rows), dim3(64), lds, stream, g);
     else
-        hipLaunchKernelGGL((bwd_dkv_kernel<unsigned short, float>), dim3((unsigned)rows), dim3(64), 0, stream, g);
+        hipLaunchKernelGGL((bwd_dkv_kernel<unsigned short, float>), dim3((unsigned)rows), dim3(64), lds, stream, g);
     return hipGetLastError();
 }
 

@@ -53,11 +53,13 @@ struct BwdArgs {
     void *dq, *dk, *dv;
 };
 size_t bwd_simple_lds_bytes(const Args &a, int dtype);
+size_t bwd_dkv_lds_bytes(const Args &a, int dtype);
 hipError_t launch_bwd_dq_simple(const BwdArgs &g, int dtype, hipStream_t stream);
 hipError_t launch_bwd_dkv_simple(const BwdArgs &g, int dtype, hipStream_t stream);
 // Matrix-core kernel for dq: bf16, D == 128, single shared prefix.
 bool bwd_mfma_supported(const Args &a, int dtype);
 hipError_t launch_bwd_dq_mfma(const BwdArgs &g, hipStream_t stream);
+hipError_t launch_bwd_dkv_mfma(const BwdArgs &g, hipStream_t stream);
 
 // Simple path: one wavefront per query row. dtype 0 = f32 storage (fp64 arithmetic),
 // 1 = bf16 storage (fp32 arithmetic). Returns the HIP launch status.

@@ -285,34 +285,23 @@ __device__ inline void pv_from_scratch(const Ctx &X, const uintx4 (&vstep)[4], b
         o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[dt], pfj, o[dt], 0, 0, 0);
 }
 
-// Normalise and store one block (the division by the softmax denominator of Eq. 2); padded
-// rows are stored as zero.  In the accumulators a lane holds scattered 4-element pieces of its
-// row; stored like that, every memory request would carry 16 bytes.  So the block goes through
-// the wavefront's scratch tile in two passes (output columns 0..63, then 64..127), written by
-// the owners of the rows and read back so that 8 consecutive lanes store 128 contiguous bytes
-// of one row.  Scratch layout: row*128 + ((chunk ^ row%8) * 16), chunk = 16 bytes.
-__device__ inline void store_block(const Args &a, const Ctx &X, int r0, const Row &row, bool rvalid, float m, float l,
-                                   const floatx16 (&o)[4])
+// Stores a 32 x 128 block held as O^T accumulators (lane column = row of the block), scaled by
+// inv and rounded to bf16; rows with rvalid false are stored as zero.  In the accumulators a
+// lane holds scattered 4-element pieces of its row; stored like that, every memory request
+// would carry 16 bytes.  So the block goes through the wavefront's scratch tile in two passes
+// (output columns 0..63, then 64..127), written by the owners of the rows and read back so that
+// 8 consecutive lanes store 128 contiguous bytes of one row.  This lane stores rows
+// 8*u + lane/8 (u = 0..3): dst[u] points at column 8*(lane%8) of that row, dst_ok[u] says
+// whether the row exists.  Scratch layout: row*128 + ((chunk ^ row%8) * 16), chunk = 16 bytes.
+// FIRST_PASS, LAST_PASS: the passes to run (0..1: all 128 columns; p..p: only columns 64p..64p+63).
+template <int FIRST_PASS = 0, int LAST_PASS = 1>
+__device__ inline void store_rows(const Ctx &X, unsigned short *const (&dst)[4], const bool (&dst_ok)[4], bool rvalid,
+                                  float inv, const floatx16 (&o)[4])
 {
     typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
     typedef __attribute__((address_space(3))) uintx2 lds_u64;
-    const float ltot = l + __shfl_xor(l, 32, 64);
-    const float inv = 1.0f / ltot;
-    // rows this lane stores: 8*u + lane/8 for u = 0..3, 16 bytes at chunk lane%8 of each pass
-    unsigned short *dst[4];
-    bool dst_ok[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int r = r0 + 8 * u + (X.lane >> 3);
-        dst_ok[u] = r < X.Mtot;
-        const unsigned rr = dst_ok[u] ? r : X.Mtot - 1;
-        const unsigned tok = fdiv(rr, a.div_g), gq = rr - tok * a.G;
-        const unsigned bl = fdiv(tok, a.div_s), i = tok - bl * a.S;
-        dst[u] = reinterpret_cast<unsigned short *>(a.out) + (long long)(X.cand0 + bl) * a.o_sb + (long long)i * a.o_ss +
-                 (long long)(X.head * a.G + gq) * a.o_sh + 8 * (X.lane & 7);
-    }
-#pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
+    for (int pass = FIRST_PASS; pass <= LAST_PASS; ++pass) {
 #pragma unroll
         for (int dl = 0; dl < 2; ++dl)
 #pragma unroll
@@ -332,13 +321,35 @@ __device__ inline void store_block(const Args &a, const Ctx &X, int r0, const Ro
             const int rl = 8 * u + (X.lane >> 3);
             const uintx4 v = *(lds_u128 *)(X.scr + rl * 128 + (((X.lane & 7) ^ (rl & 7)) << 4));
             if (dst_ok[u])
-                // the output is written once and not read again here: streaming stores keep it
-                // from piling up in L2, where it would wait for the write-back at the kernel's end
+                // written once and not read again here: streaming stores keep the result from
+                // piling up in L2, where it would wait for the write-back at the kernel's end
                 __builtin_nontemporal_store(v, reinterpret_cast<uintx4 *>(dst[u] + 64 * pass));
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
     }
+}
+
+// Normalise and store one block of the output (the division by the softmax denominator of
+// Eq. 2); padded rows are stored as zero.
+__device__ inline void store_block(const Args &a, const Ctx &X, int r0, const Row &row, bool rvalid, float m, float l,
+                                   const floatx16 (&o)[4])
+{
+    const float ltot = l + __shfl_xor(l, 32, 64);
+    const float inv = 1.0f / ltot;
+    unsigned short *dst[4];
+    bool dst_ok[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int r = r0 + 8 * u + (X.lane >> 3);
+        dst_ok[u] = r < X.Mtot;
+        const unsigned rr = dst_ok[u] ? r : X.Mtot - 1;
+        const unsigned tok = fdiv(rr, a.div_g), gq = rr - tok * a.G;
+        const unsigned bl = fdiv(tok, a.div_s), i = tok - bl * a.S;
+        dst[u] = reinterpret_cast<unsigned short *>(a.out) + (long long)(X.cand0 + bl) * a.o_sb + (long long)i * a.o_ss +
+                 (long long)(X.head * a.G + gq) * a.o_sh + 8 * (X.lane & 7);
+    }
+    store_rows(X, dst, dst_ok, rvalid, inv, o);
     if (row.rin && a.lse && X.h == 0)
         a.lse[((long long)row.rb * a.Hq + row.rh) * a.S + row.ri] =
             rvalid ? (m + __builtin_log2f(ltot)) * kLn2 : -INFINITY;
