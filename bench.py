@@ -97,6 +97,99 @@ def cpu_baseline_multi(inp, budget_s=12.0):
                       f"round; all heads), {t_total:.1f} s of oracle time"}
 
 
+def bench_backward(args):
+    """One step = one pskv_attn_bwd call (gradients with respect to q, k_suf, v_suf from out, lse
+    and dout, everything resident in HBM).  Prints one JSON line of the same form."""
+    import numpy as np
+    import torch
+    from paper_2603_13420_amd import binding as pk, inputs as gen
+    import parity_util as pu
+    w = gen.WORKLOADS[args.workload]
+    inp = gen.make_inputs(w, pad="zero", workers=16)
+    l = inp.suf_len.astype(np.int64)
+    e = 2 if w.dtype == "bf16" else 4
+    vis_pre, vis_suf = int((l * w.P).sum()), int((l * (l + 1) // 2).sum())
+    # s and dp once per visible pair, then dq (all pairs), dk and dv (suffix pairs): 2 flop per multiply-add
+    flops = w.Hq * 2 * w.D * (3 * vis_pre + 5 * vis_suf)
+    bytes_ = int(l.sum()) * (4 * w.Hq + 4 * w.Hkv) * w.D * e + int(l.sum()) * w.Hq * 4 + 2 * w.P * w.Hkv * w.D * e
+    nsets = args.sets or 2
+    base = pu.to_device(inp)
+    dout_host, dout64 = pu.make_dout(inp, w.seed + 7)
+    dout0 = (torch.from_numpy(dout_host).view(torch.bfloat16) if w.dtype == "bf16" else torch.from_numpy(dout_host)).to("cuda:0")
+    dout0 = torch.nan_to_num(dout0, nan=0.0)
+    sets = []
+    for s_ in range(nsets):
+        d = base if s_ == 0 else {k: (v.clone() if k in ("q", "k_suf", "v_suf") else v) for k, v in base.items()}
+        lse = torch.empty((w.B, w.Hq, w.S), dtype=torch.float32, device="cuda:0")
+        out = pk.pskv_attn_fwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], lse=lse,
+                               scale=inp.scale)
+        sets.append(dict(d, out=out, lse=lse, dout=dout0.clone(), dq=torch.empty_like(d["q"]),
+                         dk=torch.empty_like(d["k_suf"]), dv=torch.empty_like(d["k_suf"])))
+    torch.cuda.synchronize()
+
+    def call(i):
+        d = sets[i]
+        pk.pskv_attn_bwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], d["out"], d["lse"],
+                         d["dout"], dq=d["dq"], dk_suf=d["dk"], dv_suf=d["dv"], impl=args.impl, scale=inp.scale)
+
+    steps, warmup = min(args.steps, 400), min(args.warmup, 100)
+    for i in range(warmup):
+        call(i % nsets)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(steps):
+        call(i % nsets)
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    kern_ms = ev0.elapsed_time(ev1) / steps
+    cand = np.array([0, w.B - 1])
+    sub = inp.take(cand)
+    rq, rk, rv = pu.oracle_bwd(sub, dout64[cand])
+    sel = torch.from_numpy(cand).to("cuda:0")
+    valid = np.arange(w.S)[None, :] < sub.suf_len[:, None]
+    chk = {n: pu.compare_grad(pu.out_to_f64(sets[0][key][sel]), r, valid, w.dtype, f"bench self-check {n}")
+           for n, key, r in (("dq", "dq", rq), ("dk_suf", "dk", rk), ("dv_suf", "dv", rv))}
+    mfma = w.dtype == "bf16" and args.impl != "simple"
+    compute = {"bound": "mfma" if mfma else "alu", "achieved": flops / (kern_ms * 1e-3) / 1e12,
+               "peak": PEAK_BF16_TFLOPS if mfma else (PEAK_F64_TFLOPS if w.dtype == "f32" else 157.3), "unit": "TFLOP/s",
+               "alg_flops_per_step": flops}
+    compute["frac"] = compute["achieved"] / compute["peak"]
+    hbm = {"bound": "hbm", "achieved": bytes_ / (kern_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+           "alg_bytes_per_step": bytes_}
+    hbm["frac"] = hbm["achieved"] / hbm["peak"]
+    roof, other = (hbm, compute) if bytes_ / (PEAK_HBM_GBS * 1e9) >= flops / (compute["peak"] * 1e12) else (compute, hbm)
+    roof["traffic"] = None
+    roof["kernel_ms"] = kern_ms
+    line = {"metric": "candidate suffixes/sec per attention layer, backward pass", "value": w.B / (ms_per_step * 1e-3),
+            "unit": "candidates/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "bf16" if mfma else ("f64" if w.dtype == "f32" else "f32"), "data": "synthetic",
+            "config": {"workload": w.name, "pass": "backward", "B": w.B, "P": w.P, "S": w.S,
+                       "suffix_len": [w.len_lo, w.len_hi], "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "impl": args.impl,
+                       "buffer_sets": nsets, "seed": w.seed},
+            "roofline": roof, "roofline_" + other["bound"]: other, "self_check": chk}
+    if not args.no_cpu_baseline:
+        from oracle import pskv_oracle as orc
+        t_total, done, n = 0.0, 0, 4
+        while t_total < 12.0:
+            first = done % w.B
+            n = min(n, w.B - first)
+            c = np.arange(first, first + n)
+            sb = inp.take(c)
+            t1 = time.perf_counter()
+            pu.oracle_bwd(sb, dout64[c])
+            t_total += time.perf_counter() - t1
+            done += n
+            n = int(max(1, min(w.B, done / t_total * max(12.0 - t_total, 0.0) / 2 + 1)))
+        line["cpu_baseline"] = {"value": done / t_total, "unit": "candidates/s", "cores": orc.threads(), "kind": "oracle",
+                                "sample": f"{done} candidates of {w.name} in order (wrapping round), backward oracle, "
+                                          f"{t_total:.1f} s"}
+    print(json.dumps(line), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -105,6 +198,8 @@ def main():
     ap.add_argument("--workload", default="gqa8b_bf16")
     ap.add_argument("--impl", default="auto")
     ap.add_argument("--sets", type=int, default=0, help="rotating input/output buffer sets (0 = auto)")
+    ap.add_argument("--backward", action="store_true",
+                    help="time the backward pass (pskv_attn_bwd: dq, dk_suf, dv_suf) instead of the forward pass")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain element-wise copy of known size (the reference that the "
@@ -135,6 +230,8 @@ def main():
                           "written_bytes_per_launch": 2 * n}), flush=True)
         return
     multi = args.workload in gen.MULTI_WORKLOADS
+    if args.backward:
+        return bench_backward(args)
     if multi:
         w = gen.MULTI_WORKLOADS[args.workload]
         inp = gen.make_multi_inputs(w, pad="zero")

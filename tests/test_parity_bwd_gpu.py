@@ -21,45 +21,7 @@ def pk():
     return binding
 
 
-def make_dout(inp, seed):
-    """Seeded N(0,1) incoming gradient in the workload's storage type, NaN on padded rows.
-    Returns (host array in storage form, float64 values for the oracle)."""
-    w = inp.w
-    rng = np.random.default_rng(seed)
-    a = rng.standard_normal(size=(w.B, w.S, w.Hq, w.D), dtype=np.float32)
-    a[np.arange(w.S)[None, :] >= inp.suf_len[:, None]] = np.nan
-    if w.dtype == "bf16":
-        bits = gen.f32_to_bf16_bits(a)
-        return bits, gen.bf16_bits_to_f32(bits).astype(np.float64)
-    return a, a.astype(np.float64)
-
-
-def compare_grad(got, ref, valid_rows, dtype, what):
-    """Same bars as the forward pass, applied to a gradient tensor [B,S,H,D]."""
-    assert not np.isnan(got).any(), f"{what}: NaN"
-    assert np.all(got[~valid_rows] == 0.0), f"{what}: padded rows must be exactly 0"
-    g, r = got[valid_rows], ref[valid_rows]
-    if g.size == 0:
-        return {"n": 0}
-    err = np.abs(g - r)
-    res = {"n": int(g.size), "max_abs": float(err.max())}
-    if dtype == "f32":
-        # Relative to the element, with a floor at 1e-2 of the tensor's largest magnitude.  A
-        # gradient element is a signed sum that may cancel to (nearly) zero, and the backward call
-        # consumes out and lse as fp32 numbers (unit round-off 6e-8): a perturbation of lse by
-        # 6e-8 |lse| moves every weight of the row by about 3e-7 of itself, hence the sum by about
-        # 1e-7 of the magnitude of its terms however small the sum itself comes out.
-        floor = 1e-2 * float(np.abs(r).max())
-        res["max_rel"] = float((err / np.maximum(np.abs(r), floor)).max())
-        assert res["max_rel"] <= pu.F32_REL, f"{what}: relative error {res['max_rel']:.3e}"
-    else:
-        sd = float(r.std())
-        bound = pu.BF16_REL * np.abs(r) + pu.BF16_TIGHT_STD * sd
-        res["std_ref"] = sd
-        res["tight_ratio"] = float((err / np.maximum(bound, 1e-300)).max())
-        assert res["max_abs"] <= pu.BF16_ABS * max(1.0, sd), f"{what}: max abs error {res['max_abs']:.3e}"
-        assert res["tight_ratio"] <= 1.0, f"{what}: |err| / (2e-2 std + 2^-7|ref|) = {res['tight_ratio']:.3f}"
-    return res
+make_dout, compare_grad = pu.make_dout, pu.compare_grad
 
 
 def run_bwd(pk, inp, impl="auto", what=""):
