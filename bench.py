@@ -200,6 +200,11 @@ def main():
     ap.add_argument("--sets", type=int, default=0, help="rotating input/output buffer sets (0 = auto)")
     ap.add_argument("--backward", action="store_true",
                     help="time the backward pass (pskv_attn_bwd: dq, dk_suf, dv_suf) instead of the forward pass")
+    ap.add_argument("--baseline", default="none", choices=["none", "standard_kv", "lazy_expand"],
+                    help="run the paper's comparison layouts through the same kernels instead of the shared prefix: "
+                         "standard_kv = prefix K/V physically repeated per candidate and kept resident (Eq. 3); "
+                         "lazy_expand = the compact prefix expanded into a per-layer workspace inside every step "
+                         "(App. F.5/F.6)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain element-wise copy of known size (the reference that the "
@@ -256,8 +261,24 @@ def main():
 
     stream = torch.cuda.current_stream().cuda_stream
 
+    # Comparison layouts (single-prefix workloads only): every candidate becomes its own
+    # "instruction" with a private copy of the prefix, which is what a Standard KV cache holds.
+    expand_src = None
+    if args.baseline != "none":
+        assert not multi and w.P > 0, "--baseline applies to the single-prefix workloads"
+        kexp = torch.empty((w.B, w.P, w.Hkv, w.D), dtype=base["k_pre"].dtype, device="cuda:0")
+        vexp = torch.empty_like(kexp)
+        expand_src = (base["k_pre"][None].expand_as(kexp), base["v_pre"][None].expand_as(vexp))
+        kexp.copy_(expand_src[0])
+        vexp.copy_(expand_src[1])
+        for d in sets:
+            d["k_pre"], d["v_pre"], d["pre_len"] = kexp, vexp, None
+        multi_call = True
+    else:
+        multi_call = multi
+
     # arguments marshalled once per buffer set: the timed loop is one foreign call per step
-    if multi:
+    if multi_call:
         prepared = [pk.PreparedMultiCall(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["pre_len"],
                                          d["suf_len"], d["out"], impl=args.impl, scale=inp.scale, stream=stream)
                     for d in sets]
@@ -265,8 +286,14 @@ def main():
         prepared = [pk.PreparedCall(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], d["out"],
                                     impl=args.impl, scale=inp.scale, stream=stream) for d in sets]
 
-    def call(i):
-        prepared[i]()
+    if args.baseline == "lazy_expand":
+        def call(i):
+            kexp.copy_(expand_src[0])   # the per-layer expansion of the compact prefix ...
+            vexp.copy_(expand_src[1])
+            prepared[i]()               # ... then attention over the expanded workspace
+    else:
+        def call(i):
+            prepared[i]()
 
     for i in range(args.warmup):
         call(i % nsets)
@@ -292,7 +319,7 @@ def main():
     kern_ms = ev_ms
     # For comparison, launches timed one at a time by the library's own event-bracketed helper.
     isolated_ms = None
-    if not multi:
+    if not multi_call:
         per_set = [pk.pskv_attn_fwd_timed(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"],
                                           d["suf_len"], d["out"], impl=args.impl, scale=inp.scale, iters=1,
                                           stream=stream)
@@ -331,7 +358,7 @@ def main():
     t_compute = flops / (compute["peak"] * 1e12)
     t_hbm = bytes_ / (PEAK_HBM_GBS * 1e9)
     roof, other = (hbm, compute) if t_hbm >= t_compute else (compute, hbm)
-    tr = HBM_TRAFFIC.get(w.name) if args.impl == "auto" else None
+    tr = HBM_TRAFFIC.get(w.name) if args.impl == "auto" and args.baseline == "none" else None
     roof["traffic"] = (tr["fetch_kib"] * tr["fetch_scale"] + tr["write_kib"] * tr["write_scale"]) * 1024 if tr else None
     roof["traffic_unit"] = "bytes per launch"
     roof["kernel_ms"] = kern_ms
@@ -346,7 +373,12 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "P": w.P, "S": w.S, "suffix_len": [w.len_lo, w.len_hi],
                    "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "impl": args.impl, "buffer_sets": nsets,
-                   "seed": w.seed, **({"instructions": w.Np, "candidates_per_instruction": w.C,
+                   "seed": w.seed, "prefix_layout": args.baseline if args.baseline != "none" else "shared (PSKV)",
+                   "prefix_kv_bytes_resident": (2 * w.P * w.Hkv * w.D * e * (w.B if args.baseline == "standard_kv" else 1)
+                                                if not multi else 2 * w.Np * w.P * w.Hkv * w.D * e),
+                   "prefix_kv_bytes_transient_per_layer": (2 * w.P * w.Hkv * w.D * e * w.B
+                                                           if args.baseline == "lazy_expand" else 0),
+                   **({"instructions": w.Np, "candidates_per_instruction": w.C,
                                        "prefix_len": [w.pre_lo, w.pre_hi]} if multi else {})},
         "achieved_tflops": flops / (ms_per_step * 1e-3) / 1e12,
         "event_ms_per_step": ev_ms,
