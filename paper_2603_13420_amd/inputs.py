@@ -2,7 +2,7 @@
 
 This module produces *data only*: tensor shapes, lengths and N(0,1) values with the
 shapes of the paper's workloads (prompt of roughly 80-250 tokens as the shared prefix,
-suffix-side segments of 20-64 tokens, MHA 32/32 and GQA 32/8 head layouts, head
+suffix-side segments of 20-160 tokens, MHA 32/32, GQA 32/8 and 28/4 head layouts, head
 dimension 128; Table 1 and Table 8 of the paper).  It contains none of the method's
 arithmetic, so both the CPU oracle's tests and the HIP path's tests may draw from it.
 
@@ -49,6 +49,12 @@ WORKLOADS: Dict[str, Workload] = {w.name: w for w in [
     Workload("gqa8b_bf16",     1024, 256,  24, 16, 24, 32,  8, 128, "bf16", 2),
     Workload("longprefix_bf16", 256, 2048, 32, 32, 32, 32,  8, 128, "bf16", 3),
     Workload("mha13b_bf16",    4096, 512,  64, 32, 64, 40, 40, 128, "bf16", 4),
+    # The scoring workload with the chat template's tail and the target appended to the
+    # suffix (Sec. 3.1: the decoded segment is suffix + target): about 20 + 93 + a few dozen
+    # tokens after a prompt of about 80-130, on the 32/8 and the 28/4 (group of 7, Table 8)
+    # head layouts.
+    Workload("ldec_gqa8b_bf16", 256, 128, 160, 128, 160, 32, 8, 128, "bf16", 5),
+    Workload("ldec_qwen7b_bf16", 256, 128, 160, 128, 160, 28, 4, 128, "bf16", 6),
 ]}
 
 

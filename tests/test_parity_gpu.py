@@ -190,7 +190,8 @@ def sampled_candidates(inp, n, rng):
     return np.array(sorted(picks))[:max(n, 6)]
 
 
-@pytest.mark.parametrize("name,nsample", [("longprefix_bf16", 24), ("mha13b_bf16", 48)])
+@pytest.mark.parametrize("name,nsample", [("longprefix_bf16", 24), ("mha13b_bf16", 48),
+                                          ("ldec_gqa8b_bf16", 12), ("ldec_qwen7b_bf16", 12)])
 def test_large_shapes_full_size_sampled_compare(pk, name, nsample):
     """Run at full size in the benchmark's launch configuration; the oracle recomputes a sample
     of candidates one by one (a candidate depends only on the prefix and itself), and every
