@@ -391,6 +391,297 @@ void stream_pipelined_kernel(Args a, int npasses)
         }
 }
 
+// ------------------------------------------------------------------------------------------
+// Candidate passes: suffix-side segments of several 32-key tiles (suffix, template tail and
+// target together, Sec. 3.1).  Here the causal part is no longer a small correction after the
+// prefix, and fetching a candidate's suffix K/V per wavefront, one exposed round trip per tile,
+// dominates.  So a pass is cut out of ONE candidate: (candidate, KV head, group of up to 8 of the
+// candidate's S*G/32 row blocks), and the ring simply goes on after the last prefix tile with
+// the 32-key tiles of that candidate's own suffix K/V, up to the last key any row of the pass
+// sees.  Every tile, prefix or suffix, is then staged once per pass by all 512 threads, several
+// tiles ahead of its use, and every step is a step of the same three-stage pipeline; a step
+// whose tile has keys some row does not see (ragged last prefix tile, suffix tiles at or past
+// the row's own position) takes the masked form of the step, the limit being per row.
+// A tile wholly in a row's future gives that row weights of exactly zero.
+//
+// Pass ids are laid out so that the groups of one (candidate, KV head) unit run at the same
+// time on compute units of one XCD (workgroup ids go round the XCDs): the unit's suffix K/V is
+// then fetched from HBM once and found in that XCD's L2 by the other groups.
+// Preconditions (launcher): those of the pipelined passes above, and S*ks_stride_s*2 < 2^31.
+// ------------------------------------------------------------------------------------------
+struct CandShape {
+    int nblk_c; // 32-row blocks per candidate (S*G/32)
+    int ngrp;   // passes per (candidate, KV head) unit
+    int bpp;    // blocks per pass (the last pass of a unit may hold fewer)
+};
+
+struct CandPass {
+    int vh, head, cand0; // as in Pass
+    int b;               // candidate (global index)
+    int cblk0, cblk_last; // first and last block of the pass within the candidate
+    int blk;             // this wavefront's block in the instruction's row space (clamped)
+    bool exists;         // the unit exists (unit ids are padded to a multiple of 8)
+    bool active;         // the wavefront has a block
+};
+
+__device__ inline CandPass make_cand_pass(const Args &a, const CandShape &cs, int p, int npasses, int wave)
+{
+    CandPass ps;
+    const int pc = p < npasses ? p : npasses - 1;
+    const int q = pc >> 3, x = pc & 7;
+    const int uq = q / cs.ngrp, grp = q - uq * cs.ngrp;
+    const int units = a.B * a.Hkv;
+    int u = uq * 8 + x;
+    ps.exists = p < npasses && u < units;
+    u = u < units ? u : units - 1;
+    ps.b = u / a.Hkv;
+    ps.head = u - ps.b * a.Hkv;
+    const int n = ps.b / a.C;
+    ps.vh = n * a.Hkv + ps.head;
+    ps.cand0 = n * a.C;
+    ps.cblk0 = grp * cs.bpp;
+    const int rest = cs.nblk_c - ps.cblk0;
+    const int nb = rest < cs.bpp ? rest : cs.bpp;
+    ps.cblk_last = ps.cblk0 + nb - 1;
+    ps.active = ps.exists && wave < nb;
+    const int cblk = ps.cblk0 + wave;
+    ps.blk = (ps.b - ps.cand0) * cs.nblk_c + (cblk < ps.cblk_last ? cblk : ps.cblk_last);
+    return ps;
+}
+
+struct CandStager {
+    const unsigned char *kp, *vp;       // prefix K and V of the pass's instruction and head
+    const unsigned char *ks, *vs;       // suffix K and V of the pass's candidate and head
+    unsigned k_off, v_off;              // prefix: this thread's chunk within a full tile, bytes
+    unsigned k_off_last, v_off_last;    // ... within the last prefix tile (rows clamped into the prefix)
+    unsigned tile_stride;               // bytes from one prefix tile to the next
+    int k_row, v_row;                   // suffix: this thread's rows within a tile ...
+    unsigned k_col, v_col, row_stride;  // ... byte offsets of its chunks within a row, bytes per row
+    int Tp;                             // prefix tiles
+    int last;                           // index of the pass's last tile, prefix and suffix tiles counted together
+    int skmax;                          // last suffix key any row of the pass sees
+};
+
+// Tile kt of the pass (clamped to its last tile).  Suffix rows past skmax are fetched from row
+// skmax: no valid row sees them, finite data is all that is needed.
+__device__ inline void cand_stage_load(const CandStager &g, int kt, uintx4 &kv, uintx4 &vv)
+{
+    const int u = kt < g.last ? kt : g.last;
+    if (u < g.Tp) {
+        const unsigned base = (unsigned)u * g.tile_stride;
+        const bool lastp = u == g.Tp - 1;
+        kv = *reinterpret_cast<const uintx4 *>(g.kp + (base + (lastp ? g.k_off_last : g.k_off)));
+        vv = *reinterpret_cast<const uintx4 *>(g.vp + (base + (lastp ? g.v_off_last : g.v_off)));
+    } else {
+        const int j0 = (u - g.Tp) * kTileKeys;
+        const int kr = j0 + g.k_row < g.skmax ? j0 + g.k_row : g.skmax;
+        const int vr = j0 + g.v_row < g.skmax ? j0 + g.v_row : g.skmax;
+        kv = *reinterpret_cast<const uintx4 *>(g.ks + ((unsigned)kr * g.row_stride + g.k_col));
+        vv = *reinterpret_cast<const uintx4 *>(g.vs + ((unsigned)vr * g.row_stride + g.v_col));
+    }
+}
+
+// O^T += V^T P^T for one tile whose V image is in the ring.
+__device__ inline void pv_tile(lds_u8 *v_img, const uintx4 (&pp)[2], floatx16 (&o)[4])
+{
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+        o[ks & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_fragment(v_img, ks & 3, ks >> 2), as_bf16x8(pp[ks >> 2]),
+                                                            o[ks & 3], 0, 0, 0);
+}
+
+__global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
+void stream_candidate_kernel(Args a, int npasses, CandShape cs)
+{
+    extern __shared__ __align__(16) unsigned char smem_generic[];
+    lds_u8 *smem = (lds_u8 *)smem_generic;
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    Ctx X = make_stream_ctx(a, smem, tid);
+    auto kimg = [&](int t) { return X.k_lane + (t & (kRing - 1)) * kSlotBytes; };
+    auto vimg = [&](int t) { return X.v_lane + (t & (kRing - 1)) * kSlotBytes; };
+    auto stage_write = [&](int kt, const uintx4 &kv, const uintx4 &vv) {
+        lds_u8 *slot = smem + (kt & (kRing - 1)) * kSlotBytes + tid * 16;
+        *(lds_u128 *)slot = kv;
+        *(lds_u128 *)(slot + kTileBytes) = vv;
+    };
+
+    CandStager g;
+    const TileSlot ts = make_tile_slot(tid);
+    g.k_off = (unsigned)(ts.k_row * a.kp_sp + ts.k_chunk * 8) * 2u;
+    g.v_off = (unsigned)(ts.v_row * a.kp_sp + ts.v_chunk * 8) * 2u;
+    g.tile_stride = (unsigned)(kTileKeys * a.kp_sp) * 2u;
+    g.k_row = ts.k_row;
+    g.v_row = ts.v_row;
+    g.k_col = (unsigned)ts.k_chunk * 16u;
+    g.v_col = (unsigned)ts.v_chunk * 16u;
+    g.row_stride = (unsigned)a.ks_ss * 2u;
+
+    bool wg_bad = false, wg_short = false;
+    int p = blockIdx.x;
+    CandPass ps = make_cand_pass(a, cs, p, npasses, wave);
+    Row nxt = decode_row(a, X, ps.blk, ps.head, ps.cand0);
+    uintx4 q[8]; // this pass's Q fragments until their last use, then the next pass's
+    load_q(a, X, nxt, q);
+
+    while (p < npasses) {
+        set_vhead(a, X, ps.vh);
+        const int Tp = (X.P + kTileKeys - 1) / kTileKeys;
+        const int len = len_uniform(a, ps.b);
+        const int i_lo = (int)fdiv(ps.cblk0 * kBlockRows, a.div_g); // first suffix position of the pass
+        const bool nothing = !ps.exists || i_lo >= len;             // no unit, or nothing but padding
+        if (nothing || Tp < kMinTiles) {
+            if (!nothing)
+                wg_short = true; // prefix too short for the pipeline: left to the general sweep below
+            else if (ps.active)
+                store_zero_block(a, X, nxt);
+            p += gridDim.x;
+            ps = make_cand_pass(a, cs, p, npasses, wave);
+            nxt = decode_row(a, X, ps.blk, ps.head, ps.cand0);
+            load_q(a, X, nxt, q);
+            continue;
+        }
+        const int i_hi = (int)fdiv(ps.cblk_last * kBlockRows + kBlockRows - 1, a.div_g);
+        const int skmax = i_hi < len - 1 ? i_hi : len - 1;
+        const int T = Tp + skmax / kTileKeys + 1;
+        {
+            const int nlast = X.P - (Tp - 1) * kTileKeys; // rows of the last prefix tile, 1..32
+            const int kr = ts.k_row < nlast ? ts.k_row : nlast - 1, vr = ts.v_row < nlast ? ts.v_row : nlast - 1;
+            g.k_off_last = (unsigned)(kr * a.kp_sp + ts.k_chunk * 8) * 2u;
+            g.v_off_last = (unsigned)(vr * a.kp_sp + ts.v_chunk * 8) * 2u;
+            g.Tp = Tp;
+            g.last = T - 1;
+            g.skmax = skmax;
+            g.kp = reinterpret_cast<const unsigned char *>(X.kpg);
+            g.vp = reinterpret_cast<const unsigned char *>(X.vpg);
+            g.ks = reinterpret_cast<const unsigned char *>(X.ksg + (long long)ps.b * a.ks_sb);
+            g.vs = reinterpret_cast<const unsigned char *>(X.vsg + (long long)ps.b * a.ks_sb);
+        }
+        const int r0 = ps.blk * kBlockRows;
+        const bool active = ps.active;
+        const Row row = nxt;
+        const bool rvalid = active && row.rin && (int)row.ri < clamp_len(a, row.rlen);
+
+        // The ring is free here (the barrier that ended the previous pass).  Tiles 0..3 go in at once.
+        uintx4 kv0, vv0, kv1, vv1;
+        {
+            uintx4 kv2, vv2, kv3, vv3;
+            cand_stage_load(g, 0, kv0, vv0);
+            cand_stage_load(g, 1, kv1, vv1);
+            cand_stage_load(g, 2, kv2, vv2);
+            cand_stage_load(g, 3, kv3, vv3);
+            stage_write(0, kv0, vv0);
+            stage_write(1, kv1, vv1);
+            stage_write(2, kv2, vv2);
+            stage_write(3, kv3, vv3);
+        }
+        cand_stage_load(g, 4, kv0, vv0);
+        cand_stage_load(g, 5, kv1, vv1);
+        __syncthreads();
+
+        // Visibility limit of tile t for this lane's row, as pipe_tile takes it: element e (key
+        // offset 8*(e/4) + e%4 + 4*h within the tile) is visible iff its offset without the
+        // 4*h is <= lim.  Prefix tiles are fully visible but for the end of a ragged last one;
+        // suffix tile j holds keys 32*j.. of which the row sees those up to its own position.
+        const int lim_suffix = (int)row.ri - 4 * X.h + Tp * kTileKeys;
+        const int lim_last_prefix = X.P - (Tp - 1) * kTileKeys - 1 - 4 * X.h;
+        auto lim_of = [&](int t) { return t >= Tp ? lim_suffix - t * kTileKeys : (t == Tp - 1 ? lim_last_prefix : 1 << 20); };
+        const int tm = X.P / kTileKeys; // first tile with keys that some row does not see (>= 2)
+
+        // ---- first prefix tile: scores, reference maximum ----
+        floatx16 sA, sB;
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            sA[e] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+            sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*(lds_u128 *)(kimg(0) + ks * 1024)), as_bf16x8(q[ks]), sA,
+                                                         0, 0, 0);
+        Pre pre;
+#pragma unroll
+        for (int i = 0; i < kDist; ++i)
+            pre.k[i] = *(lds_u128 *)(kimg(1) + i * 1024);
+        float m = sA[0];
+#pragma unroll
+        for (int e = 1; e < 16; ++e)
+            m = fmaxf(m, sA[e]);
+        m = fmaxf(m, __shfl_xor(m, 32, 64)) * X.c;
+        float l = 0.f;
+        floatx16 o[4];
+        uintx4 pA[2], pB[2];
+        uintx4 nokf[8]; // stands in for the register K fragments no step here uses
+
+        pipe_tile<true, false, false, false, false, true, true>(kimg(1), nokf, vimg(0), kimg(2), vimg(0), pre, q, sA, sB,
+                                                                X.c, m, 0, l, pA, pA, o);
+        pipe_tile<true, false, true, true, false, true, true>(kimg(2), nokf, vimg(0), kimg(3 < T ? 3 : T - 1), vimg(1), pre, q,
+                                                              sB, sA, X.c, m, 0, l, pA, pB, o);
+#define PSKV_CAND_PAIR(t, MASKED)                                                                                      \
+    do {                                                                                                               \
+        pipe_tile<true, false, true, false, MASKED, true, true>(kimg((t) + 1), nokf, vimg((t) - 1), kimg((t) + 2),     \
+                                                                vimg(t), pre, q, sA, sB, X.c, m, lim_of(t), l, pB, pA, \
+                                                                o);                                                    \
+        pipe_tile<true, false, true, false, MASKED, true, true>(kimg((t) + 2), nokf, vimg(t),                          \
+                                                                kimg((t) + 3 < T ? (t) + 3 : T - 1), vimg((t) + 1),    \
+                                                                pre, q, sB, sA, X.c, m, lim_of((t) + 1), l, pA, pB,    \
+                                                                o);                                                    \
+    } while (0)
+        int t = 2;
+        for (; t + 1 <= T - 2 && t + 1 < tm; t += 2) { // pairs of fully visible tiles
+            stage_write(t + 2, kv0, vv0);
+            stage_write(t + 3, kv1, vv1);
+            cand_stage_load(g, t + 4, kv0, vv0);
+            cand_stage_load(g, t + 5, kv1, vv1);
+            __syncthreads();
+            PSKV_CAND_PAIR(t, false);
+        }
+        for (; t + 1 <= T - 2; t += 2) {
+            stage_write(t + 2, kv0, vv0);
+            stage_write(t + 3, kv1, vv1);
+            cand_stage_load(g, t + 4, kv0, vv0);
+            cand_stage_load(g, t + 5, kv1, vv1);
+            __syncthreads();
+            PSKV_CAND_PAIR(t, true);
+        }
+#undef PSKV_CAND_PAIR
+        if (t <= T - 2) { // one step left over: do it and put scores and weights back in their places
+            pipe_tile<true, false, true, false, true, false, true>(kimg(t + 1), nokf, vimg(t - 1), kimg(T - 1), vimg(t), pre,
+                                                                   q, sA, sB, X.c, m, lim_of(t), l, pB, pA, o);
+            sA = sB;
+            pB[0] = pA[0];
+            pB[1] = pA[1];
+        }
+
+        // Q has been used for the last time: the next pass's Q takes its place
+        p += gridDim.x;
+        ps = make_cand_pass(a, cs, p, npasses, wave);
+        nxt = decode_row(a, X, ps.blk, ps.head, ps.cand0);
+        load_q(a, X, nxt, q);
+
+        // ---- last tile: its weights under the value product of the tile before, then its own ----
+        pipe_tile<false, false, true, false, true, false, false>(kimg(0), nokf, vimg(T - 2), kimg(0), vimg(0), pre, q, sA, sA,
+                                                                 X.c, m, lim_of(T - 1), l, pB, pA, o);
+        pv_tile(vimg(T - 1), pA, o);
+
+        const bool bad = __builtin_amdgcn_ballot_w64(rvalid && !(l < kBig)) != 0;
+        if (active)
+            store_block(a, X, r0, row, rvalid, m, l, o);
+        if (X.lane == 0)
+            *(lds_int *)X.scr = bad ? 1 : 0;
+        __syncthreads(); // ends the pass: the ring is free, the verdicts are visible
+        wg_bad |= __builtin_amdgcn_ballot_w64(*(lds_int *)(smem + kRing * kSlotBytes + (X.lane & (kNW - 1)) * kScrBytes) !=
+                                              0) != 0;
+    }
+
+    // The general sweep, as in the pipelined kernel above.
+    if (wg_bad || wg_short)
+        for (int p2 = blockIdx.x; p2 < npasses; p2 += gridDim.x) {
+            const CandPass ps2 = make_cand_pass(a, cs, p2, npasses, wave);
+            set_vhead(a, X, ps2.vh);
+            if (ps2.exists && (wg_bad || (X.P + kTileKeys - 1) / kTileKeys < kMinTiles))
+                general_pass(a, X, smem, tid, ps2.vh, ps2.blk, ps2.active);
+        }
+}
+
 int device_cu_count(hipError_t &e)
 {
     static int num_cu = 0;
@@ -408,6 +699,9 @@ int device_cu_count(hipError_t &e)
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e == hipSuccess)
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(stream_pipelined_kernel<false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(stream_candidate_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess)
             return 0;
@@ -451,6 +745,22 @@ hipError_t launch_stream(const Args &a, hipStream_t stream)
     const unsigned grid = (unsigned)(npasses < num_cu ? npasses : num_cu);
     const bool pipelined = ((long long)a.S * a.G) % kBlockRows == 0 && max_tiles >= kMinTiles &&
                            (long long)a.P * a.kp_sp * 2 < 0x7fffffffLL;
+    // Long suffix-side segments whose candidates fill most of a workgroup's eight wavefronts
+    // take the candidate passes.
+    if (pipelined && a.S > kTileKeys && (long long)a.S * a.ks_ss * 2 < 0x7fffffffLL) {
+        CandShape cs;
+        const long long nblk_c = (long long)a.S * a.G / kBlockRows;
+        cs.nblk_c = (int)nblk_c;
+        cs.ngrp = (int)((nblk_c + kNW - 1) / kNW);
+        cs.bpp = (cs.nblk_c + cs.ngrp - 1) / cs.ngrp;
+        const long long units = (long long)a.B * a.Hkv;
+        const long long cpasses = (units + 7) / 8 * 8 * cs.ngrp;
+        if (nblk_c * 10 >= (long long)cs.ngrp * kNW * 6 && cpasses <= 0x7fffffffLL - 8) {
+            const unsigned cgrid = (unsigned)(cpasses < num_cu ? cpasses : num_cu);
+            hipLaunchKernelGGL(stream_candidate_kernel, dim3(cgrid), dim3(kNW * 64), kLdsBytes, stream, a, (int)cpasses, cs);
+            return hipGetLastError();
+        }
+    }
     if (!pipelined)
         hipLaunchKernelGGL(stream_general_kernel, dim3(grid), dim3(kNW * 64), kLdsBytes, stream, a, (int)npasses);
     else if (a.S <= kTileKeys)

@@ -62,6 +62,11 @@ def test_tiny_f32_full(pk):
     (9, 289, 32, 0, 32, 4, 1),      # ... ragged last prefix tile, last pass with idle wavefronts
     (3, 420, 64, 20, 64, 2, 2),     # ... two suffix steps, second row block sometimes all padding
     (2, 1000, 96, 1, 96, 3, 3),     # ... three suffix steps
+    (3, 300, 40, 5, 40, 8, 2),      # passes cut out of one candidate: one pass of 5 blocks, 6 units of 8
+    (2, 130, 160, 100, 160, 8, 2),  # ... 20 blocks in three passes, five suffix tiles
+    (3, 128, 160, 0, 160, 4, 1),    # ... prefix of whole tiles; empty, short and full candidates
+    (2, 97, 96, 1, 96, 14, 2),      # ... group 7: blocks straddle suffix tiles; one-row last prefix tile
+    (9, 70, 64, 64, 64, 4, 1),      # ... more units than eight, shortest prefix the pipeline takes
 ])
 def test_small_shapes_bf16(pk, impl, B, P, S, lo, hi, Hq, Hkv):
     w = gen.custom_workload(f"small_{B}_{P}_{S}_{Hq}_{Hkv}", B, P, S, lo, hi, Hq, Hkv, 128, "bf16",
@@ -152,6 +157,7 @@ BF16_ONE, BF16_EIGHT = 0x3F80, 0x4100
     (3, 700, 40, 33, 40, 2, 2),     # long prefix: general streaming kernel
     (3, 700, 32, 20, 32, 8, 2),     # long prefix: pipelined streaming kernel, one suffix step
     (3, 400, 64, 40, 64, 2, 2),     # ... several suffix steps
+    (3, 200, 96, 70, 96, 8, 2),     # passes cut out of one candidate
 ])
 def test_scores_far_above_the_first_tile(pk, impl, B, P, S, lo, hi, Hq, Hkv):
     """A late prefix key and a late suffix key whose scores exceed everything seen before by

@@ -60,6 +60,7 @@ def run_multi(pk, inp, impl, what=""):
     (3, 4, 700, 150, 700, 32, 5, 32, 8, 2),     # streamed prefixes, one suffix step; short ones take the general sweep
     (2, 3, 520, 300, 520, 64, 20, 64, 2, 2),    # streamed, two suffix steps
     (3, 2, 300, 0, 300, 33, 5, 33, 14, 2),      # streamed, general kernel (odd sizes, group 7)
+    (4, 3, 200, 20, 200, 64, 1, 64, 8, 2),      # passes cut out of one candidate; short prefixes take the general sweep
 ])
 def test_multi_small_shapes_bf16(pk, impl, Np, C, P, plo, phi, S, lo, hi, Hq, Hkv):
     w = gen.custom_multi_workload(f"multi_{Np}_{C}_{P}_{S}", Np, C, P, plo, phi, S, lo, hi, Hq, Hkv, 128, "bf16",
