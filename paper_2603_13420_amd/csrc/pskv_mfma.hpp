@@ -230,6 +230,22 @@ __device__ inline void load_q(const Args &a, const Ctx &X, const Row &x, uintx4 
         dst[ks] = ld_global16(qrow + 16 * ks);
 }
 
+// The same, with the rows known to be padding (wanted false) left out of the request - they
+// are a sixth of the query tensor at the paper's length mix - and taken as zero.
+__device__ inline void load_q(const Args &a, const Ctx &X, const Row &x, bool wanted, uintx4 (&dst)[8])
+{
+    const unsigned short *qrow = reinterpret_cast<const unsigned short *>(a.q) + (long long)x.rb * a.q_sb +
+                                 (long long)x.ri * a.q_ss + (long long)x.rh * a.q_sh + 8 * X.h;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+        dst[ks] = uintx4{0, 0, 0, 0};
+    if (wanted) {
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+            dst[ks] = ld_global16(qrow + 16 * ks);
+    }
+}
+
 // Suffix K fragments of step (candidate b, keys k0..k0+31) straight from global memory in
 // A-operand layout.  Rows past kmax are never visible: their address is clamped to row kmax
 // (and to row 0, candidate B-1, so that the loads stay in bounds even when there is no step).

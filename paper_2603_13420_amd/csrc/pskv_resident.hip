@@ -165,7 +165,7 @@ void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
     int blk = skip_padding(first_blk);
     Row nxt = decode_row(a, X, blk < nblocks ? blk : nblocks - 1);
     uintx4 q[8]; // this block's Q fragments until their last use, then the next block's
-    load_q(a, X, nxt, q);
+    load_q(a, X, nxt, (int)nxt.ri < len_uniform(a, X.cand0 + block_cand(blk < nblocks ? blk : nblocks - 1)), q);
 
     __syncthreads(); // every wavefront is done with the images of the virtual head before
     stage_prefix(a, X, T, smem, smem + max_tiles * kTileBytes, tid);
@@ -250,7 +250,7 @@ void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
         // branch would have to be waited for and copied at the join.)
         blk = skip_padding(blk + blk_stride);
         nxt = decode_row(a, X, blk < nblocks ? blk : nblocks - 1);
-        load_q(a, X, nxt, q);
+        load_q(a, X, nxt, (int)nxt.ri < len_uniform(a, X.cand0 + block_cand(blk < nblocks ? blk : nblocks - 1)), q);
 
         // ---- suffix step: causal mask and weights under the value product of the last prefix
         //      tile; then the suffix value product through the scratch tile ----
