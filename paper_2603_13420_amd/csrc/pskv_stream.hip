@@ -462,46 +462,23 @@ struct CandStager {
     int skmax;                          // last suffix key any row of the pass sees
 };
 
-// Where this thread's K and V chunks of tile kt of the pass (clamped to its last tile) lie.
-// Suffix rows past skmax are taken from row skmax: no valid row sees them, finite data is all
-// that is needed.
-__device__ inline void cand_chunk_addr(const CandStager &g, int kt, const unsigned char *&kptr, const unsigned char *&vptr)
+// Tile kt of the pass (clamped to its last tile).  Suffix rows past skmax are fetched from row
+// skmax: no valid row sees them, finite data is all that is needed.
+__device__ inline void cand_stage_load(const CandStager &g, int kt, uintx4 &kv, uintx4 &vv)
 {
     const int u = kt < g.last ? kt : g.last;
     if (u < g.Tp) {
         const unsigned base = (unsigned)u * g.tile_stride;
         const bool lastp = u == g.Tp - 1;
-        kptr = g.kp + (base + (lastp ? g.k_off_last : g.k_off));
-        vptr = g.vp + (base + (lastp ? g.v_off_last : g.v_off));
+        kv = *reinterpret_cast<const uintx4 *>(g.kp + (base + (lastp ? g.k_off_last : g.k_off)));
+        vv = *reinterpret_cast<const uintx4 *>(g.vp + (base + (lastp ? g.v_off_last : g.v_off)));
     } else {
         const int j0 = (u - g.Tp) * kTileKeys;
         const int kr = j0 + g.k_row < g.skmax ? j0 + g.k_row : g.skmax;
         const int vr = j0 + g.v_row < g.skmax ? j0 + g.v_row : g.skmax;
-        kptr = g.ks + ((unsigned)kr * g.row_stride + g.k_col);
-        vptr = g.vs + ((unsigned)vr * g.row_stride + g.v_col);
+        kv = *reinterpret_cast<const uintx4 *>(g.ks + ((unsigned)kr * g.row_stride + g.k_col));
+        vv = *reinterpret_cast<const uintx4 *>(g.vs + ((unsigned)vr * g.row_stride + g.v_col));
     }
-}
-
-// The chunks into registers, to be written into the ring later (stage_write).
-__device__ inline void cand_stage_load(const CandStager &g, int kt, uintx4 &kv, uintx4 &vv)
-{
-    const unsigned char *kptr, *vptr;
-    cand_chunk_addr(g, kt, kptr, vptr);
-    kv = *reinterpret_cast<const uintx4 *>(kptr);
-    vv = *reinterpret_cast<const uintx4 *>(vptr);
-}
-
-// The chunks straight into a ring slot, without passing through registers: the request of a
-// wavefront puts lane l's 16 bytes at (wave-uniform base) + 16*l, which is where thread tid's
-// chunk belongs in a fragment-major image (image + 16*tid).  slot_wave = slot + 1024*wave.
-// The data is in LDS once this thread's vector-memory counter says the requests are complete.
-__device__ inline void cand_stage_direct(const CandStager &g, int kt, lds_u8 *slot_wave)
-{
-    typedef __attribute__((address_space(1))) const unsigned char glb_u8;
-    const unsigned char *kptr, *vptr;
-    cand_chunk_addr(g, kt, kptr, vptr);
-    __builtin_amdgcn_global_load_lds((glb_u8 *)kptr, slot_wave, 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((glb_u8 *)vptr, slot_wave + kTileBytes, 16, 0, 0);
 }
 
 // O^T += V^T P^T for one tile whose V image is in the ring.
@@ -585,17 +562,22 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
         const Row row = nxt;
         const bool rvalid = active && row.rin && (int)row.ri < clamp_len(a, row.rlen);
 
-        // The ring is free here (the barrier that ended the previous pass).  The first eight
-        // tiles of the pass - all of them, for the shapes this kernel is meant for - are requested
-        // at once, straight into their slots: one round trip to memory per pass instead of one
-        // per pair of steps.
-#pragma unroll
-        for (int u = 0; u < kRing; ++u)
-            if (u < T)
-                cand_stage_direct(g, u, smem + u * kSlotBytes + wave * 1024);
-        __builtin_amdgcn_s_waitcnt(0x0F70); // vmcnt(0): this thread's requests have landed
-        __syncthreads();                    // ... and so have everybody else's
-        uintx4 kv0, vv0, kv1, vv1;          // staging registers of the tiles past the first eight
+        // The ring is free here (the barrier that ended the previous pass).  Tiles 0..3 go in at once.
+        uintx4 kv0, vv0, kv1, vv1;
+        {
+            uintx4 kv2, vv2, kv3, vv3;
+            cand_stage_load(g, 0, kv0, vv0);
+            cand_stage_load(g, 1, kv1, vv1);
+            cand_stage_load(g, 2, kv2, vv2);
+            cand_stage_load(g, 3, kv3, vv3);
+            stage_write(0, kv0, vv0);
+            stage_write(1, kv1, vv1);
+            stage_write(2, kv2, vv2);
+            stage_write(3, kv3, vv3);
+        }
+        cand_stage_load(g, 4, kv0, vv0);
+        cand_stage_load(g, 5, kv1, vv1);
+        __syncthreads();
 
         // Visibility limit of tile t for this lane's row, as pipe_tile takes it: element e (key
         // offset 8*(e/4) + e%4 + 4*h within the tile) is visible iff its offset without the
@@ -644,30 +626,22 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
                                                                 o);                                                    \
     } while (0)
         int t = 2;
-        // Tiles past the first eight follow the ring protocol of the pipelined passes above: at the
-        // top of the pair (t, t+1) tiles t+2 and t+3 are written, tiles t+4 and t+5 requested.
-#define PSKV_CAND_STAGE(t)                                                                                             \
-    do {                                                                                                               \
-        if ((t) + 2 >= kRing) {                                                                                        \
-            stage_write((t) + 2, kv0, vv0);                                                                            \
-            stage_write((t) + 3, kv1, vv1);                                                                            \
-        }                                                                                                              \
-        if ((t) + 4 >= kRing) {                                                                                        \
-            cand_stage_load(g, (t) + 4, kv0, vv0);                                                                     \
-            cand_stage_load(g, (t) + 5, kv1, vv1);                                                                     \
-        }                                                                                                              \
-        if ((t) + 2 >= kRing)                                                                                          \
-            __syncthreads();                                                                                           \
-    } while (0)
         for (; t + 1 <= T - 2 && t + 1 < tm; t += 2) { // pairs of fully visible tiles
-            PSKV_CAND_STAGE(t);
+            stage_write(t + 2, kv0, vv0);
+            stage_write(t + 3, kv1, vv1);
+            cand_stage_load(g, t + 4, kv0, vv0);
+            cand_stage_load(g, t + 5, kv1, vv1);
+            __syncthreads();
             PSKV_CAND_PAIR(t, false);
         }
         for (; t + 1 <= T - 2; t += 2) {
-            PSKV_CAND_STAGE(t);
+            stage_write(t + 2, kv0, vv0);
+            stage_write(t + 3, kv1, vv1);
+            cand_stage_load(g, t + 4, kv0, vv0);
+            cand_stage_load(g, t + 5, kv1, vv1);
+            __syncthreads();
             PSKV_CAND_PAIR(t, true);
         }
-#undef PSKV_CAND_STAGE
 #undef PSKV_CAND_PAIR
         if (t <= T - 2) { // one step left over: do it and put scores and weights back in their places
             pipe_tile<true, false, true, false, true, false, true>(kimg(t + 1), nokf, vimg(t - 1), kimg(T - 1), vimg(t), pre,
