@@ -44,6 +44,14 @@ struct Args {
     long long o_sb, o_ss, o_sh;
 };
 
+// Whether one candidate's part of q, of out and of the suffix K/V each spans less than 2^31
+// bytes (16-bit elements), so that kernels may address rows within a candidate by 32-bit offsets.
+inline bool block_offsets_fit(const Args &a)
+{
+    const long long lim = 0x7fffffffLL / 2;
+    return a.S * a.q_ss + a.Hq * a.q_sh < lim && a.S * a.o_ss + a.Hq * a.o_sh < lim && a.S * a.ks_ss + a.Hkv * a.ks_sh < lim;
+}
+
 // Backward pass: the forward problem (f.out and f.lse are the forward results, read-only here),
 // the incoming gradient dout (laid out like out) and the three outputs (dq like q; dk, dv like
 // k_suf, v_suf).

@@ -230,22 +230,6 @@ __device__ inline void load_q(const Args &a, const Ctx &X, const Row &x, uintx4 
         dst[ks] = ld_global16(qrow + 16 * ks);
 }
 
-// The same, with the rows known to be padding (wanted false) left out of the request - they
-// are a sixth of the query tensor at the paper's length mix - and taken as zero.
-__device__ inline void load_q(const Args &a, const Ctx &X, const Row &x, bool wanted, uintx4 (&dst)[8])
-{
-    const unsigned short *qrow = reinterpret_cast<const unsigned short *>(a.q) + (long long)x.rb * a.q_sb +
-                                 (long long)x.ri * a.q_ss + (long long)x.rh * a.q_sh + 8 * X.h;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks)
-        dst[ks] = uintx4{0, 0, 0, 0};
-    if (wanted) {
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
-            dst[ks] = ld_global16(qrow + 16 * ks);
-    }
-}
-
 // Suffix K fragments of step (candidate b, keys k0..k0+31) straight from global memory in
 // A-operand layout.  Rows past kmax are never visible: their address is clamped to row kmax
 // (and to row 0, candidate B-1, so that the loads stay in bounds even when there is no step).
@@ -383,6 +367,111 @@ __device__ inline void store_zero_block(const Args &a, const Ctx &X, const Row &
         __builtin_nontemporal_store(uintx4{0, 0, 0, 0}, reinterpret_cast<uintx4 *>(orow + 64 * X.h + 8 * u));
     if (a.lse && X.h == 0)
         a.lse[((long long)row.rb * a.Hq + row.rh) * a.S + row.ri] = -INFINITY;
+}
+
+// ------------------------------------------------------------------------------------------
+// Bookkeeping for a 32-row block that lies inside one candidate (S*G a multiple of 32).  The
+// candidate is then the same for all lanes, so everything that depends on it - its length, its
+// offset into q, out, lse and the suffix K/V - is scalar, and what is left per lane (position
+// and head within the candidate) fits 32-bit byte offsets.  Precondition (launchers): one
+// candidate's part of q, of out and of the suffix K/V spans less than 2^31 bytes.
+// ------------------------------------------------------------------------------------------
+struct BlockRows {
+    int b;          // candidate (global index), wave-uniform
+    int len;        // its clamped suffix length, wave-uniform
+    int ri, rh;     // this lane's suffix position and query head
+    unsigned q_off; // byte offset of the lane's row from the candidate's first q row
+    unsigned o_off; // ... from the candidate's first out row
+};
+
+__device__ inline BlockRows decode_block(const Args &a, const Ctx &X, int blk, int head, int cand0)
+{
+    BlockRows x;
+    const unsigned r0 = (unsigned)blk * kBlockRows;
+    const int bl = __builtin_amdgcn_readfirstlane((int)fdiv(fdiv(r0, a.div_g), a.div_s)); // candidate within the instruction
+    x.b = cand0 + bl;
+    x.len = len_uniform(a, x.b);
+    const unsigned r = r0 + X.c32;
+    const unsigned tok = fdiv(r, a.div_g), gq = r - tok * a.G;
+    x.ri = (int)tok - bl * a.S;
+    x.rh = head * a.G + (int)gq;
+    // Rows past the candidate's length take the query row of its last position instead of their
+    // own: the padding (a sixth of the query tensor at the paper's length mix) is never fetched,
+    // and what such rows compute is finite and stored as zero.
+    const int rq = x.ri < x.len ? x.ri : (x.len > 0 ? x.len - 1 : 0);
+    x.q_off = ((unsigned)rq * (unsigned)a.q_ss + (unsigned)x.rh * (unsigned)a.q_sh) * 2u;
+    x.o_off = ((unsigned)x.ri * (unsigned)a.o_ss + (unsigned)x.rh * (unsigned)a.o_sh) * 2u;
+    return x;
+}
+
+// Q fragments of the block (layout as in load_q).
+__device__ inline void load_q_block(const Args &a, const Ctx &X, const BlockRows &x, uintx4 (&dst)[8])
+{
+    const unsigned char *base = reinterpret_cast<const unsigned char *>(a.q) + (long long)x.b * a.q_sb * 2;
+    const unsigned char *qrow = base + (x.q_off + 16u * X.h);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+        dst[ks] = *reinterpret_cast<const uintx4 *>(qrow + 32 * ks);
+}
+
+// Suffix K fragments and V rows of keys k0..k0+31 of the block's candidate (layouts and
+// clamping as in load_suffix_k and load_suffix_v; kmax >= 0).
+__device__ inline void load_suffix_k_block(const Args &a, const Ctx &X, int b, int k0, int kmax, uintx4 (&kf)[8])
+{
+    const unsigned char *base = reinterpret_cast<const unsigned char *>(X.ksg) + (long long)b * a.ks_sb * 2;
+    const int krow = k0 + X.c32 < kmax ? k0 + X.c32 : kmax;
+    const unsigned char *kp = base + ((unsigned)krow * (unsigned)a.ks_ss * 2u + 16u * X.h);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)
+        kf[ks] = *reinterpret_cast<const uintx4 *>(kp + 32 * ks);
+}
+
+__device__ inline void load_suffix_v_block(const Args &a, const Ctx &X, int b, int k0, int kmax, uintx4 (&vf)[2][4])
+{
+    const unsigned char *base = reinterpret_cast<const unsigned char *>(X.vsg) + (long long)b * a.ks_sb * 2;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int frag = 2 * it + X.h; // fragment (dt = frag >> 1, u = frag & 1)
+            int key = k0 + 16 * j + 8 * (frag & 1) + X.sv_row_lo;
+            key = key < kmax ? key : kmax;
+            vf[j][it] = *reinterpret_cast<const uintx4 *>(
+                base + ((unsigned)key * (unsigned)a.ks_ss * 2u + (unsigned)(4 * (frag >> 1) + X.sv_chunk_lo) * 16u));
+        }
+}
+
+// Normalise and store the block (as store_block).  Lane l stores rows 8*u + l/8 of the block,
+// whose offsets it takes from the lanes that own those rows.
+__device__ inline void store_block_rows(const Args &a, const Ctx &X, const BlockRows &x, float m, float l,
+                                        const floatx16 (&o)[4])
+{
+    const float ltot = l + __shfl_xor(l, 32, 64);
+    const float inv = 1.0f / ltot;
+    const bool rvalid = x.ri < x.len;
+    unsigned char *base = reinterpret_cast<unsigned char *>(a.out) + (long long)x.b * a.o_sb * 2;
+    unsigned short *dst[4];
+    bool dst_ok[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const unsigned off = (unsigned)__shfl((int)x.o_off, 8 * u + (X.lane >> 3), 64);
+        dst[u] = reinterpret_cast<unsigned short *>(base + (off + 16u * (X.lane & 7)));
+        dst_ok[u] = true;
+    }
+    store_rows(X, dst, dst_ok, rvalid, inv, o);
+    if (a.lse && X.h == 0)
+        a.lse[((long long)x.b * a.Hq + x.rh) * a.S + x.ri] = rvalid ? (m + __builtin_log2f(ltot)) * kLn2 : -INFINITY;
+}
+
+// Zeros for a block that holds nothing but padding.
+__device__ inline void store_zero_block_rows(const Args &a, const Ctx &X, const BlockRows &x)
+{
+    unsigned char *orow = reinterpret_cast<unsigned char *>(a.out) + (long long)x.b * a.o_sb * 2 + x.o_off;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+        __builtin_nontemporal_store(uintx4{0, 0, 0, 0}, reinterpret_cast<uintx4 *>(orow + 128 * X.h + 16 * u));
+    if (a.lse && X.h == 0)
+        a.lse[((long long)x.b * a.Hq + x.rh) * a.S + x.ri] = -INFINITY;
 }
 
 // Which 16-byte chunk of a row-major 32-key tile thread tid of a 512-thread group fetches so

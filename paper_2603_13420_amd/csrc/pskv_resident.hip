@@ -149,7 +149,7 @@ void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
     // on the way are stored as zeros here and now.
     auto skip_padding = [&](int blk) {
         while (blk < nblocks && block_i_lo(blk) >= len_uniform(a, X.cand0 + block_cand(blk))) {
-            store_zero_block(a, X, decode_row(a, X, blk));
+            store_zero_block_rows(a, X, decode_block(a, X, blk, X.head, X.cand0));
             blk += blk_stride;
         }
         return blk;
@@ -163,9 +163,9 @@ void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
     const int first_blk = (blockIdx.x / vh_slots) * kNW + __builtin_amdgcn_readfirstlane(tid >> 6);
     bool any_bad = false;
     int blk = skip_padding(first_blk);
-    Row nxt = decode_row(a, X, blk < nblocks ? blk : nblocks - 1);
+    BlockRows nxt = decode_block(a, X, blk < nblocks ? blk : nblocks - 1, X.head, X.cand0);
     uintx4 q[8]; // this block's Q fragments until their last use, then the next block's
-    load_q(a, X, nxt, (int)nxt.ri < len_uniform(a, X.cand0 + block_cand(blk < nblocks ? blk : nblocks - 1)), q);
+    load_q_block(a, X, nxt, q);
 
     __syncthreads(); // every wavefront is done with the images of the virtual head before
     stage_prefix(a, X, T, smem, smem + max_tiles * kTileBytes, tid);
@@ -178,18 +178,13 @@ void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
     }
 
     while (blk < nblocks) {
-        const int r0 = blk * kBlockRows;
-        const Row row = nxt;
-        const bool rvalid = row.rin && (int)row.ri < clamp_len(a, row.rlen);
-
-        // the block's suffix step: candidate sb, keys 0..skmax
-        const int sb = block_cand(blk);
-        const int i_hi = (int)fdiv(r0 + kBlockRows - 1, a.div_g) - sb * a.S;
-        const int len = len_uniform(a, X.cand0 + sb);
-        const int skmax = i_hi < len - 1 ? i_hi : len - 1;
+        const BlockRows row = nxt;
+        // the block's suffix step: keys 0..skmax of its candidate
+        const int i_hi = (int)fdiv(blk * kBlockRows + kBlockRows - 1, a.div_g) - (row.b - X.cand0) * a.S;
+        const int skmax = i_hi < row.len - 1 ? i_hi : row.len - 1;
         // Loads are retired in issue order, so what is needed last is requested first.
         uintx4 skf[8], svf[2][4];
-        load_suffix_k(a, X, X.cand0 + sb, 0, skmax, skf);
+        load_suffix_k_block(a, X, row.b, 0, skmax, skf);
 
         // ---- first prefix tile: scores, reference maximum ----
         floatx16 sA, sB; // raw scores of the current and of the next tile, roles alternating
@@ -240,7 +235,7 @@ void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
                 if (8 * (e >> 2) + (e & 3) >= nv)
                     sA[e] = -INFINITY;
         }
-        load_suffix_v(a, X, X.cand0 + sb, 0, skmax, svf); // one step ahead of its use
+        load_suffix_v_block(a, X, row.b, 0, skmax, svf); // one step ahead of its use
         // ---- last prefix tile: the "next scores" are the suffix scores, from the K registers ----
         pipe_tile<true, true, true, false, false, false, true>(kimg(0), skf, vimg(T - 2), kimg(0), vimg(T - 1), pre, q, sA,
                                                                sB, X.c, m, 0, l, pB, pA, o);
@@ -249,8 +244,8 @@ void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
         // (Requested unconditionally, for a clamped block index past the end: a load under a
         // branch would have to be waited for and copied at the join.)
         blk = skip_padding(blk + blk_stride);
-        nxt = decode_row(a, X, blk < nblocks ? blk : nblocks - 1);
-        load_q(a, X, nxt, (int)nxt.ri < len_uniform(a, X.cand0 + block_cand(blk < nblocks ? blk : nblocks - 1)), q);
+        nxt = decode_block(a, X, blk < nblocks ? blk : nblocks - 1, X.head, X.cand0);
+        load_q_block(a, X, nxt, q);
 
         // ---- suffix step: causal mask and weights under the value product of the last prefix
         //      tile; then the suffix value product through the scratch tile ----
@@ -260,8 +255,8 @@ void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
         pv_from_scratch(X, svf[0], as_bf16x8(pB[0]), o);
         pv_from_scratch(X, svf[1], as_bf16x8(pB[1]), o);
 
-        any_bad |= __builtin_amdgcn_ballot_w64(rvalid && !(l < kBig)) != 0;
-        store_block(a, X, r0, row, rvalid, m, l, o);
+        any_bad |= __builtin_amdgcn_ballot_w64(row.ri < row.len && !(l < kBig)) != 0;
+        store_block_rows(a, X, row, m, l, o);
     }
 
     // Rare: some row met scores far above its first tile's maximum.  Whatever this wavefront
@@ -312,7 +307,8 @@ hipError_t launch_resident(const Args &a, hipStream_t stream)
         per_vh = useful;
     const unsigned grid = (unsigned)(per_vh * vh_slots);
     const size_t lds = (size_t)2 * max_tiles * kTileBytes + kNW * kScrBytes;
-    const bool pipelined = ((long long)a.S * a.G) % kBlockRows == 0 && a.S <= kTileKeys && max_tiles >= 3;
+    const bool pipelined = ((long long)a.S * a.G) % kBlockRows == 0 && a.S <= kTileKeys && max_tiles >= 3 &&
+                           block_offsets_fit(a);
     if (pipelined)
         hipLaunchKernelGGL(resident_pipelined_kernel, dim3(grid), dim3(kNW * 64), lds, stream, a, (int)per_vh,
                            (int)vh_slots, max_tiles);
