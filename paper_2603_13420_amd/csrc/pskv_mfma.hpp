@@ -62,6 +62,14 @@ __device__ inline bf16x8 as_bf16x8(uintx4 v)
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// a * b with the rule that zero times anything, infinities and NaN included, is zero.
+__device__ inline float mul_zero_wins(float a, float b)
+{
+    float r;
+    asm("v_mul_legacy_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
 __device__ inline unsigned pack_bf16(float lo, float hi)
 {
     floatx2 f = {lo, hi};
@@ -300,6 +308,7 @@ __device__ inline void store_rows(const Ctx &X, unsigned short *const (&dst)[4],
 {
     typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
     typedef __attribute__((address_space(3))) uintx2 lds_u64;
+    const float scale = rvalid ? inv : 0.f;
 #pragma unroll
     for (int pass = FIRST_PASS; pass <= LAST_PASS; ++pass) {
 #pragma unroll
@@ -307,11 +316,9 @@ __device__ inline void store_rows(const Ctx &X, unsigned short *const (&dst)[4],
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
                 const int dt = 2 * pass + dl;
-                uintx2 w = {0u, 0u};
-                if (rvalid) { // a padded row may carry NaN; it is stored as zero
-                    w[0] = pack_bf16(o[dt][4 * kk + 0] * inv, o[dt][4 * kk + 1] * inv);
-                    w[1] = pack_bf16(o[dt][4 * kk + 2] * inv, o[dt][4 * kk + 3] * inv);
-                }
+                // a padded row may carry NaN or infinities; scaled by a zero that wins it is stored as zero
+                const uintx2 w = {pack_bf16(mul_zero_wins(o[dt][4 * kk + 0], scale), mul_zero_wins(o[dt][4 * kk + 1], scale)),
+                                  pack_bf16(mul_zero_wins(o[dt][4 * kk + 2], scale), mul_zero_wins(o[dt][4 * kk + 3], scale))};
                 *(lds_u64 *)(X.scr + X.c32 * 128 + (((4 * dl + kk) ^ (X.c32 & 7)) << 4) + 8 * X.h) = w;
             }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
