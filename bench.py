@@ -49,9 +49,10 @@ def alg_counts(w, suf_len, pre_len=None):
 # the factor by which the same counter under- or over-reads a plain copy kernel of known size.
 # Offline measurements: the commands and raw readings are in profiles/*_hbm_traffic.txt.
 HBM_TRAFFIC = {
-    "gqa8b_bf16": {"fetch_kib": 145320.0, "fetch_scale": 2.0, "write_kib": 205771.0, "write_scale": 1.0},
-    "longprefix_bf16": {"fetch_kib": 63436.0, "fetch_scale": 2.0, "write_kib": 67074.0, "write_scale": 1.0},
-    "multi8_gqa8b_bf16": {"fetch_kib": 147373.0, "fetch_scale": 2.0, "write_kib": 208369.0, "write_scale": 1.0},
+    "gqa8b_bf16": {"fetch_kib": 135377.0, "fetch_scale": 2.0, "write_kib": 213490.0, "write_scale": 1.0},
+    "ldec_gqa8b_bf16": {"fetch_kib": 238028.0, "fetch_scale": 2.0, "write_kib": 327680.0, "write_scale": 1.0},
+    "longprefix_bf16": {"fetch_kib": 63228.5, "fetch_scale": 2.0, "write_kib": 67083.7, "write_scale": 1.0},
+    "multi8_gqa8b_bf16": {"fetch_kib": 136042.9, "fetch_scale": 2.0, "write_kib": 213675.2, "write_scale": 1.0},
 }
 
 
