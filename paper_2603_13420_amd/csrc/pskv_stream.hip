@@ -14,11 +14,13 @@
 // consecutive heads, so the workgroups of one XCD keep returning to the same few heads and
 // find them in that XCD's L2.
 //
-// Two kernels.  The pipelined one (every 32-row block inside one candidate) is the software
+// Three kernels.  The pipelined one (every 32-row block inside one candidate) is the software
 // pipeline of the resident-prefix kernel with the tile images taken from the ring, the suffix
 // handled after the prefix, and a fixed per-row reference maximum; when a row turns out to
 // need rescaling, the workgroup repeats its passes on the general path.  The general one
-// (any shape) is the classic online softmax, one tile at a time.
+// (any shape) is the classic online softmax, one tile at a time.  The third (further down) is
+// for suffix-side segments of several tiles: its passes are cut out of one candidate, whose own
+// suffix K/V then goes through the ring like the prefix.
 // Operand layouts and the pieces shared with the resident kernels are in pskv_mfma.hpp.
 #include "pskv_mfma.hpp"
 
