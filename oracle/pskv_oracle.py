@@ -132,6 +132,30 @@ def attn_bwd(q, k_suf, v_suf, k_pre, v_pre, suf_len, dout, scale: float, dtype: 
     return dq, dk, dv
 
 
+def attn_bwd_multi(q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, dout, scale: float, dtype: str,
+                   nthreads: int = 0):
+    """Backward pass of the batched multi-instruction form (Sec. 4.3).  The instructions are
+    independent problems: instruction n is the single-prefix problem made of its own C = B / Np
+    candidates and of the real rows of its prefix, the last pre_len[n] of the Pp padded ones
+    (App. F.1: prefixes are left-padded), so its gradient is attn_bwd of exactly that problem.
+    Returns (dq, dk_suf, dv_suf), float64."""
+    B = q.shape[0]
+    Np, Pp = k_pre.shape[0], k_pre.shape[1]
+    if Np == 0 or B % Np != 0:
+        raise ValueError("the number of candidates must be a multiple of the number of instructions")
+    C = B // Np
+    dq = np.empty(q.shape, dtype=np.float64)
+    dk = np.empty(k_suf.shape, dtype=np.float64)
+    dv = np.empty(v_suf.shape, dtype=np.float64)
+    for n in range(Np):
+        pl = Pp if pre_len is None else min(max(int(pre_len[n]), 0), Pp)
+        cs = slice(n * C, (n + 1) * C)
+        sl = None if suf_len is None else np.asarray(suf_len)[cs]
+        dq[cs], dk[cs], dv[cs] = attn_bwd(q[cs], k_suf[cs], v_suf[cs], k_pre[n, Pp - pl:], v_pre[n, Pp - pl:], sl,
+                                          np.asarray(dout)[cs], scale, dtype, nthreads)
+    return dq, dk, dv
+
+
 def attn_multi(q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, scale: float, dtype: str,
                want_lse: bool = False, want_probs: bool = False, nthreads: int = 0):
     """Batched multi-instruction form (Sec. 4.3): k_pre, v_pre are [Np,Pp,Hkv,D], left-padded,

@@ -125,3 +125,64 @@ def test_bf16_inputs_are_widened_exactly():
     a = orc.attn_bwd(*bits, sl, do, 0.35, "bf16")
     b = orc.attn_bwd(*wide, sl, do, 0.35, "f64")
     assert all(np.array_equal(x, y) for x, y in zip(a, b))
+
+
+def multi_problem(rng, Np, C, Pp, S, Hq, Hkv, D):
+    B = Np * C
+    q = rng.standard_normal((B, S, Hq, D))
+    ks = rng.standard_normal((B, S, Hkv, D))
+    vs = rng.standard_normal((B, S, Hkv, D))
+    kp = rng.standard_normal((Np, Pp, Hkv, D))
+    vp = rng.standard_normal((Np, Pp, Hkv, D))
+    pl = rng.integers(0, Pp + 1, size=Np).astype(np.int32)
+    pl[0] = Pp
+    sl = rng.integers(0, S + 1, size=B).astype(np.int32)
+    sl[0] = S
+    do = rng.standard_normal((B, S, Hq, D))
+    return q, ks, vs, kp, vp, pl, sl, do
+
+
+def test_multi_instruction_backward_is_the_derivative_of_the_multi_instruction_forward():
+    """Central differences of the (separately pinned) multi-instruction forward oracle, including
+    with respect to prefix padding rows, which must not matter."""
+    rng = np.random.default_rng(77)
+    Np, C, Pp, S, Hq, Hkv, D = 3, 2, 4, 3, 2, 1, 3
+    q, ks, vs, kp, vp, pl, sl, do = multi_problem(rng, Np, C, Pp, S, Hq, Hkv, D)
+    pl[1] = 0
+    scale = 0.7
+    dq, dk, dv = orc.attn_bwd_multi(q, ks, vs, kp, vp, pl, sl, do, scale, "f64")
+
+    def loss(q_, ks_, vs_):
+        return float((do * orc.attn_multi(q_, ks_, vs_, kp, vp, pl, sl, scale, "f64")).sum())
+
+    eps = 1e-6
+    for name, grad, idx in (("q", dq, 0), ("k", dk, 1), ("v", dv, 2)):
+        args = [q, ks, vs]
+        base = args[idx]
+        num = np.zeros_like(base)
+        it = np.nditer(base, flags=["multi_index"])
+        for _ in it:
+            mi = it.multi_index
+            hi, lo = base.copy(), base.copy()
+            hi[mi] += eps
+            lo[mi] -= eps
+            a_hi, a_lo = list(args), list(args)
+            a_hi[idx], a_lo[idx] = hi, lo
+            num[mi] = (loss(*a_hi) - loss(*a_lo)) / (2 * eps)
+        np.testing.assert_allclose(grad, num, rtol=0, atol=2e-8, err_msg=name)
+    # what lies in the left padding of a prefix reaches no gradient
+    kp2, vp2 = kp.copy(), vp.copy()
+    for n in range(Np):
+        kp2[n, :Pp - pl[n]] = np.nan
+        vp2[n, :Pp - pl[n]] = np.nan
+    for a_, b_ in zip((dq, dk, dv), orc.attn_bwd_multi(q, ks, vs, kp2, vp2, pl, sl, do, scale, "f64")):
+        assert np.array_equal(a_, b_)
+
+
+def test_multi_instruction_backward_with_one_instruction_is_the_single_prefix_backward():
+    rng = np.random.default_rng(78)
+    q, ks, vs, kp, vp, sl, do = problem(rng, 3, 5, 4, 4, 2, 4)
+    one = orc.attn_bwd(q, ks, vs, kp, vp, sl, do, 0.5, "f64")
+    multi = orc.attn_bwd_multi(q, ks, vs, kp[None], vp[None], None, sl, do, 0.5, "f64")
+    for a_, b_ in zip(one, multi):
+        assert np.array_equal(a_, b_)
