@@ -206,9 +206,8 @@ pskv_status pskv_attn_fwd_multi(const pskv_multi_params *p,
  *
  * Padded rows of dout are ignored.  Same ownership, stream and error rules as the forward call;
  * outputs must not alias inputs or one another.  p->impl: SIMPLE selects the vector-ALU kernels
- * (fp64 arithmetic for f32 tensors, fp32 for bf16); AUTO computes dq on the matrix cores when the
- * tensors are bf16 with D == 128 (dk_suf and dv_suf, a small share of the work, stay on the
- * vector ALU); MFMA insists on that and is refused otherwise.
+ * (fp64 arithmetic for f32 tensors, fp32 for bf16); AUTO uses the matrix-core kernels when the
+ * tensors are bf16 with D == 128; MFMA insists on that and is refused otherwise.
  */
 pskv_status pskv_attn_bwd(const pskv_attn_params *p,
                           const void *q, const void *k_suf, const void *v_suf,
@@ -218,6 +217,26 @@ pskv_status pskv_attn_bwd(const pskv_attn_params *p,
                           void *dq, void *dk_suf, void *dv_suf,
                           void *workspace, size_t workspace_bytes,
                           void *hip_stream);
+
+/*
+ * Backward pass of pskv_attn_fwd_multi (the batched multi-instruction form of Sec. 4.3): the
+ * instructions are independent, so candidate b's gradients are those of pskv_attn_bwd for the
+ * problem made of its instruction's candidates and the real rows of that instruction's prefix
+ * (the last pre_len[n] of the P left-padded ones, App. F.1).  Prefixes get no gradient.
+ *
+ *   k_pre, v_pre, pre_len   as for pskv_attn_fwd_multi (same params struct)
+ *   everything else         as for pskv_attn_bwd
+ *
+ * With Np == 1 and pre_len == NULL this is pskv_attn_bwd.
+ */
+pskv_status pskv_attn_bwd_multi(const pskv_multi_params *p,
+                                const void *q, const void *k_suf, const void *v_suf,
+                                const void *k_pre, const void *v_pre,
+                                const int32_t *pre_len, const int32_t *suf_len,
+                                const void *out, const float *lse, const void *dout,
+                                void *dq, void *dk_suf, void *dv_suf,
+                                void *workspace, size_t workspace_bytes,
+                                void *hip_stream);
 
 #ifdef __cplusplus
 }

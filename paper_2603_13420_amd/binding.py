@@ -19,7 +19,7 @@ _IMPL = {"auto": PSKV_IMPL_AUTO, "simple": PSKV_IMPL_SIMPLE, "mfma": PSKV_IMPL_M
 
 EXPORTS = ["pskv_version", "pskv_status_str", "pskv_last_error", "pskv_attn_fwd_workspace_bytes",
            "pskv_attn_validate", "pskv_attn_fwd", "pskv_attn_fwd_timed",
-           "pskv_attn_multi_validate", "pskv_attn_fwd_multi", "pskv_attn_bwd"]
+           "pskv_attn_multi_validate", "pskv_attn_fwd_multi", "pskv_attn_bwd", "pskv_attn_bwd_multi"]
 
 
 class pskv_attn_params(ctypes.Structure):
@@ -77,6 +77,8 @@ def load():
     lib.pskv_attn_fwd_multi.argtypes = [PM, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.pskv_attn_bwd.restype = ctypes.c_int
     lib.pskv_attn_bwd.argtypes = [P] + [vp] * 13 + [ctypes.c_size_t, vp]
+    lib.pskv_attn_bwd_multi.restype = ctypes.c_int
+    lib.pskv_attn_bwd_multi.argtypes = [PM] + [vp] * 14 + [ctypes.c_size_t, vp]
     _lib = lib
     return lib
 
@@ -328,6 +330,35 @@ def pskv_attn_bwd(q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse, dout, dq=Non
         rc = load().pskv_attn_bwd(ctypes.byref(p), _ptr(q), _ptr(k_suf), _ptr(v_suf), _ptr(k_pre), _ptr(v_pre),
                                   _ptr(suf_len), _ptr(out), _ptr(lse), _ptr(dout), _ptr(dq), _ptr(dk_suf),
                                   _ptr(dv_suf), None, 0, ctypes.c_void_p(stream))
+    if rc != PSKV_OK:
+        _raise(rc)
+    return dq, dk_suf, dv_suf
+
+
+def pskv_attn_bwd_multi(q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, out, lse, dout, dq=None, dk_suf=None,
+                        dv_suf=None, impl: str = "auto", scale: float = 0.0, stream: Optional[int] = None):
+    """Backward pass of the batched multi-instruction form (arguments as for pskv_attn_fwd_multi
+    and pskv_attn_bwd).  Returns (dq, dk_suf, dv_suf)."""
+    import torch
+    if lse is None:
+        raise ValueError("the backward pass needs the forward pass's lse")
+    p = _multi_setup(q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, out, lse, impl, scale)
+    if tuple(dout.shape) != tuple(out.shape) or dout.stride() != out.stride() or dout.dtype != q.dtype:
+        raise ValueError("dout must have the shape, strides and dtype of out")
+    dq = torch.empty_like(q) if dq is None else dq
+    dk_suf = torch.empty_like(k_suf) if dk_suf is None else dk_suf
+    dv_suf = torch.empty_like(v_suf) if dv_suf is None else dv_suf
+    if dq.shape != q.shape or dq.stride() != q.stride() or dq.dtype != q.dtype:
+        raise ValueError("dq must have the shape, strides and dtype of q")
+    for name, t in (("dk_suf", dk_suf), ("dv_suf", dv_suf)):
+        if t.shape != k_suf.shape or t.stride() != k_suf.stride() or t.dtype != q.dtype:
+            raise ValueError(f"{name} must have the shape, strides and dtype of k_suf")
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    with torch.cuda.device(q.device):
+        rc = load().pskv_attn_bwd_multi(ctypes.byref(p), _ptr(q), _ptr(k_suf), _ptr(v_suf), _ptr(k_pre), _ptr(v_pre),
+                                        _ptr(pre_len), _ptr(suf_len), _ptr(out), _ptr(lse), _ptr(dout), _ptr(dq),
+                                        _ptr(dk_suf), _ptr(dv_suf), None, 0, ctypes.c_void_p(stream))
     if rc != PSKV_OK:
         _raise(rc)
     return dq, dk_suf, dv_suf

@@ -224,17 +224,17 @@ pskv_status pskv_attn_fwd_multi(const pskv_multi_params *p, const void *q, const
                   hip_stream);
 }
 
-pskv_status pskv_attn_bwd(const pskv_attn_params *p, const void *q, const void *k_suf, const void *v_suf,
-                          const void *k_pre, const void *v_pre, const int32_t *suf_len, const void *out,
-                          const float *lse, const void *dout, void *dq, void *dk_suf, void *dv_suf,
-                          void *workspace, size_t workspace_bytes, void *hip_stream)
+// Validation and launch shared by the two backward entry points (np == 1, pre_len == NULL: one
+// shared prefix).
+static pskv_status launch_bwd(const pskv_attn_params *p, int np, int64_t kp_stride_n, const void *q, const void *k_suf,
+                              const void *v_suf, const void *k_pre, const void *v_pre, const int32_t *pre_len,
+                              const int32_t *suf_len, const void *out, const float *lse, const void *dout, void *dq,
+                              void *dk_suf, void *dv_suf, void *hip_stream)
 {
-    (void)workspace;
-    (void)workspace_bytes; // no path needs scratch
     pskv::BwdArgs g{};
     pskv::Args &a = g.f;
     bool use_mfma = false;
-    pskv_status s = resolve(p, 1, 0, a, use_mfma);
+    pskv_status s = resolve(p, np, kp_stride_n, a, use_mfma);
     if (s != PSKV_OK)
         return s;
     const bool dq_mfma = use_mfma && pskv::bwd_mfma_supported(a, p->dtype);
@@ -254,8 +254,9 @@ pskv_status pskv_attn_bwd(const pskv_attn_params *p, const void *q, const void *
     for (const void *ptr : ptrs)
         if (misaligned(ptr))
             return fail(PSKV_ERR_INVALID_ARG, "data pointer %p is not 16-byte aligned", ptr);
-    if ((reinterpret_cast<uintptr_t>(suf_len) & 3u) || (reinterpret_cast<uintptr_t>(lse) & 3u))
-        return fail(PSKV_ERR_INVALID_ARG, "suf_len and lse must be 4-byte aligned");
+    if ((reinterpret_cast<uintptr_t>(suf_len) & 3u) || (reinterpret_cast<uintptr_t>(lse) & 3u) ||
+        (reinterpret_cast<uintptr_t>(pre_len) & 3u))
+        return fail(PSKV_ERR_INVALID_ARG, "suf_len, pre_len and lse must be 4-byte aligned");
     const void *ins[] = {q, k_suf, v_suf, k_pre, v_pre, out, dout, lse};
     void *outs[] = {dq, dk_suf, dv_suf};
     for (int x = 0; x < 3; ++x) {
@@ -268,6 +269,7 @@ pskv_status pskv_attn_bwd(const pskv_attn_params *p, const void *q, const void *
     }
     a.q = q; a.ks = k_suf; a.vs = v_suf; a.kp = k_pre; a.vp = v_pre;
     a.len = suf_len;
+    a.plen = pre_len;
     a.out = const_cast<void *>(out); // read-only in every backward kernel
     a.lse = const_cast<float *>(lse);
     g.dout = dout; g.dq = dq; g.dk = dk_suf; g.dv = dv_suf;
@@ -279,6 +281,32 @@ pskv_status pskv_attn_bwd(const pskv_attn_params *p, const void *q, const void *
         return fail(PSKV_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
     g_err[0] = '\0';
     return PSKV_OK;
+}
+
+pskv_status pskv_attn_bwd(const pskv_attn_params *p, const void *q, const void *k_suf, const void *v_suf,
+                          const void *k_pre, const void *v_pre, const int32_t *suf_len, const void *out,
+                          const float *lse, const void *dout, void *dq, void *dk_suf, void *dv_suf,
+                          void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    (void)workspace;
+    (void)workspace_bytes; // no path needs scratch
+    return launch_bwd(p, 1, 0, q, k_suf, v_suf, k_pre, v_pre, nullptr, suf_len, out, lse, dout, dq, dk_suf, dv_suf,
+                      hip_stream);
+}
+
+pskv_status pskv_attn_bwd_multi(const pskv_multi_params *p, const void *q, const void *k_suf, const void *v_suf,
+                                const void *k_pre, const void *v_pre, const int32_t *pre_len, const int32_t *suf_len,
+                                const void *out, const float *lse, const void *dout, void *dq, void *dk_suf,
+                                void *dv_suf, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    (void)workspace;
+    (void)workspace_bytes; // no path needs scratch
+    if (!p)
+        return fail(PSKV_ERR_INVALID_ARG, "params is NULL");
+    if (p->reserved != 0)
+        return fail(PSKV_ERR_INVALID_ARG, "reserved field must be 0");
+    return launch_bwd(&p->base, p->Np, p->kp_stride_n, q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, out, lse, dout, dq,
+                      dk_suf, dv_suf, hip_stream);
 }
 
 pskv_status pskv_attn_fwd_timed(const pskv_attn_params *p, const void *q, const void *k_suf,

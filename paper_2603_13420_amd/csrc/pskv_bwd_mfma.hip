@@ -1,5 +1,6 @@
 // Matrix-core kernel for the query gradient of batched candidate-suffix attention on gfx950
-// (bf16 tensors, head dim 128, single shared prefix of any length, any suffix shape).
+// (bf16 tensors, head dim 128, prefix of any length - one shared prefix or one per instruction of
+// the batched multi-instruction form -, any suffix shape).
 //
 // For a query row with softmax weights p_j = exp(s_j - lse) over its visible rows
 // (prefix, then own suffix rows 0..i; derivative of Eq. 2, prefix K/V constant):
@@ -473,7 +474,7 @@ void bwd_dkv_mfma_kernel(BwdArgs g, int nunits, int nkt)
 
 bool bwd_mfma_supported(const Args &a, int dtype)
 {
-    return mfma_supported(a, dtype) && a.Np == 1 && a.plen == nullptr;
+    return mfma_supported(a, dtype);
 }
 
 hipError_t launch_bwd_dkv_mfma(const BwdArgs &g, hipStream_t stream)

@@ -82,15 +82,23 @@ __global__ __launch_bounds__(64) void bwd_dq_kernel(BwdArgs g)
     const C lse = (C)a.lse[((long long)b * a.Hq + h) * a.S + i];
     __syncthreads();
 
-    const T *kp = reinterpret_cast<const T *>(a.kp) + k * a.kp_sh;
-    const T *vp = reinterpret_cast<const T *>(a.vp) + k * a.kp_sh;
+    // the candidate's instruction and its prefix: the last P of the a.P left-padded rows (Sec. 4.3, App. F.1)
+    const int n = b / a.C;
+    int P = a.P;
+    if (a.plen) {
+        P = a.plen[n];
+        P = P < 0 ? 0 : (P > a.P ? a.P : P);
+    }
+    const long long pre_off = (long long)n * a.kp_sn + (long long)(a.P - P) * a.kp_sp + (long long)k * a.kp_sh;
+    const T *kp = reinterpret_cast<const T *>(a.kp) + pre_off;
+    const T *vp = reinterpret_cast<const T *>(a.vp) + pre_off;
     const T *ks = reinterpret_cast<const T *>(a.ks) + b * a.ks_sb + k * a.ks_sh;
     const T *vs = reinterpret_cast<const T *>(a.vs) + b * a.ks_sb + k * a.ks_sh;
-    const int nvis = a.P + i + 1; // whole prefix, then suffix rows 0..i
+    const int nvis = P + i + 1; // whole prefix, then suffix rows 0..i
 
     for (int j = lane; j < nvis; j += 64) {
-        const T *kr = j < a.P ? kp + j * a.kp_sp : ks + (j - a.P) * a.ks_ss;
-        const T *vr = j < a.P ? vp + j * a.kp_sp : vs + (j - a.P) * a.ks_ss;
+        const T *kr = j < P ? kp + j * a.kp_sp : ks + (j - P) * a.ks_ss;
+        const T *vr = j < P ? vp + j * a.kp_sp : vs + (j - P) * a.ks_ss;
         C s = 0, dp = 0;
         for (int d = 0; d < a.D; ++d) {
             s += qs[d] * (C)load_as_float(kr + d);
@@ -102,10 +110,10 @@ __global__ __launch_bounds__(64) void bwd_dq_kernel(BwdArgs g)
     __syncthreads();
     for (int d = lane; d < a.D; d += 64) {
         C acc = 0;
-        for (int j = 0; j < a.P; ++j)
+        for (int j = 0; j < P; ++j)
             acc += sc[j] * (C)load_as_float(kp + j * a.kp_sp + d);
         for (int t = 0; t <= i; ++t)
-            acc += sc[a.P + t] * (C)load_as_float(ks + t * a.ks_ss + d);
+            acc += sc[P + t] * (C)load_as_float(ks + t * a.ks_ss + d);
         store_from(dq + d, acc * (C)a.scale);
     }
 }

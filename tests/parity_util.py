@@ -23,6 +23,12 @@ F32_REL = 1e-5
 BF16_ABS = 2e-2
 BF16_TIGHT_STD = 2e-2
 BF16_REL = 2.0 ** -7
+# Gradients of bf16 problems: the backward call is handed the forward result `out` rounded to bf16
+# (unit round-off 2^-9), and <dout_row, out_row>, which enters every element of that row's dq and
+# of the dk it contributes to, inherits about 2^-9 * |dout_row| * |out_row| / sqrt(3) from it.  For a
+# row that sees only a handful of keys (|out_row| is then not averaged down) this alone is about
+# 1e-2 of the gradient's standard deviation at the worst element of 1e5, so the std term is 3e-2.
+BF16_TIGHT_STD_GRAD = 3e-2
 
 
 def to_device(inp: gen.Inputs, device="cuda:0"):
@@ -142,11 +148,14 @@ def compare_grad(got, ref, valid_rows, dtype, what):
         assert res["max_rel"] <= F32_REL, f"{what}: relative error {res['max_rel']:.3e}"
     else:
         sd = float(r.std())
-        bound = BF16_REL * np.abs(r) + BF16_TIGHT_STD * sd
+        bound = BF16_REL * np.abs(r) + BF16_TIGHT_STD_GRAD * sd
         res["std_ref"] = sd
         res["tight_ratio"] = float((err / np.maximum(bound, 1e-300)).max())
-        assert res["max_abs"] <= BF16_ABS * max(1.0, sd), f"{what}: max abs error {res['max_abs']:.3e}"
-        assert res["tight_ratio"] <= 1.0, f"{what}: |err| / (2e-2 std + 2^-7|ref|) = {res['tight_ratio']:.3f}"
+        # the absolute bar of the forward pass, for tensors whose elements are sums of many terms of
+        # order one: scaled by the tensor's spread, plus the bf16 rounding of its largest element
+        abs_bar = BF16_ABS * max(1.0, sd) + 2.0 ** -8 * float(np.abs(r).max())
+        assert res["max_abs"] <= abs_bar, f"{what}: max abs error {res['max_abs']:.3e} > {abs_bar:.3e}"
+        assert res["tight_ratio"] <= 1.0, f"{what}: |err| / (3e-2 std + 2^-7|ref|) = {res['tight_ratio']:.3f}"
     return res
 
 

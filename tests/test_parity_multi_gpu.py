@@ -113,3 +113,74 @@ def test_strided_prefix_batch_and_clamped_prefix_lengths(pk):
 def test_multi_named_workloads_full_size(pk, name):
     """The multi-instruction workloads of the benchmark at full size, every element compared."""
     run_multi(pk, gen.make_multi_inputs(gen.MULTI_WORKLOADS[name], pad="nan"), "auto")
+
+
+# ------------------------------------------------------------------------------------------
+# backward pass of the multi-instruction form
+# ------------------------------------------------------------------------------------------
+def run_multi_bwd(pk, inp, impl, what=""):
+    import torch
+    from oracle import pskv_oracle as orc
+    d = pu.to_device_multi(inp)
+    w = inp.w
+    print(f"[case] bwd {what or w.name} impl={impl} Np={w.Np} C={w.C} P={w.P} pre_len={inp.pre_len.tolist()[:8]} "
+          f"S={w.S} Hq={w.Hq} Hkv={w.Hkv} D={w.D} {w.dtype} seed={w.seed}", flush=True)
+    lse = torch.empty((w.B, w.Hq, w.S), dtype=torch.float32, device="cuda:0")
+    out = pk.pskv_attn_fwd_multi(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["pre_len"], d["suf_len"],
+                                 lse=lse, scale=inp.scale)
+    dout_host, dout64 = pu.make_dout(inp, w.seed + 7)
+    t = torch.from_numpy(dout_host)
+    dout = (t.view(torch.bfloat16) if w.dtype == "bf16" else t).to("cuda:0")
+    nan = float("nan")
+    dq, dk, dv = (torch.full_like(d["q"], nan), torch.full_like(d["k_suf"], nan), torch.full_like(d["k_suf"], nan))
+    pk.pskv_attn_bwd_multi(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["pre_len"], d["suf_len"], out, lse,
+                           dout, dq=dq, dk_suf=dk, dv_suf=dv, impl=impl, scale=inp.scale)
+    torch.cuda.synchronize()
+    rq, rk, rv = orc.attn_bwd_multi(inp.q, inp.k_suf, inp.v_suf, inp.k_pre, inp.v_pre, inp.pre_len, inp.suf_len,
+                                    np.nan_to_num(dout64, nan=0.0), inp.scale, w.dtype)
+    valid = np.arange(w.S)[None, :] < inp.suf_len[:, None]
+    res = {n: pu.compare_grad(pu.out_to_f64(g), r, valid, w.dtype, f"{what or w.name} {n}")
+           for n, g, r in (("dq", dq, rq), ("dk_suf", dk, rk), ("dv_suf", dv, rv))}
+    print(f"       {res}", flush=True)
+    return res
+
+
+@pytest.mark.parametrize("impl", ["simple", "mfma"])
+@pytest.mark.parametrize("Np,C,P,plo,phi,S,lo,hi,Hq,Hkv", [
+    (3, 4, 256, 96, 256, 24, 16, 24, 8, 2),     # the headline shape in small, three instructions
+    (5, 2, 100, 0, 100, 20, 0, 20, 4, 4),       # several candidates per block, some prefixes empty or very short
+    (3, 2, 300, 0, 300, 33, 5, 33, 14, 2),      # group 7, odd sizes
+    (2, 3, 520, 300, 520, 64, 20, 64, 2, 2),    # longer prefixes and suffix-side segments
+])
+def test_multi_bwd_small_shapes_bf16(pk, impl, Np, C, P, plo, phi, S, lo, hi, Hq, Hkv):
+    w = gen.custom_multi_workload(f"multi_bwd_{Np}_{C}_{P}_{S}", Np, C, P, plo, phi, S, lo, hi, Hq, Hkv, 128, "bf16",
+                                  index=400 + Np + P)
+    inp = gen.make_multi_inputs(w, pad="keep")
+    inp.pre_len[0] = phi
+    if plo == 0:
+        inp.pre_len[-1] = 0
+    run_multi_bwd(pk, poison_padding(inp), impl)
+
+
+def test_multi_bwd_f32(pk):
+    w = gen.custom_multi_workload("multi_bwd_f32", 3, 3, 40, 0, 40, 12, 1, 12, 4, 2, 64, "f32", index=450)
+    run_multi_bwd(pk, gen.make_multi_inputs(w, pad="nan"), "auto")
+
+
+def test_single_instruction_backward_equals_multi_with_one_instruction(pk):
+    """pskv_attn_bwd and pskv_attn_bwd_multi(Np = 1, no pre_len) are the same operation: same bits."""
+    import torch
+    w = gen.custom_workload("one_bwd", 6, 256, 24, 16, 24, 8, 2, 128, "bf16", index=460)
+    inp = gen.make_inputs(w, pad="nan")
+    d = pu.to_device(inp)
+    lse = torch.empty((w.B, w.Hq, w.S), dtype=torch.float32, device="cuda:0")
+    out = pk.pskv_attn_fwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], lse=lse, scale=inp.scale)
+    dout_host, _ = pu.make_dout(inp, 461)
+    dout = torch.from_numpy(dout_host).view(torch.bfloat16).to("cuda:0")
+    a = pk.pskv_attn_bwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], out, lse, dout,
+                         scale=inp.scale)
+    b = pk.pskv_attn_bwd_multi(d["q"], d["k_suf"], d["v_suf"], d["k_pre"][None], d["v_pre"][None], None, d["suf_len"],
+                               out, lse, dout, scale=inp.scale)
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x.view(torch.int16), y.view(torch.int16))
