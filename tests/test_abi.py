@@ -106,6 +106,37 @@ def test_fwd_refuses_null_and_misaligned_pointers_before_any_launch():
     assert rc == pk.PSKV_ERR_INVALID_ARG
 
 
+def test_bwd_refuses_bad_pointers_before_any_launch():
+    """Both backward entry points check their pointers on the host before the first HIP call."""
+    lib = pk.load()
+    p = ok(dtype="bf16", D=128)
+    a, b, c, d_ = (ctypes.c_void_p(x) for x in (0x1000, 0x2000, 0x3000, 0x4000))
+    out, lse, dout = ctypes.c_void_p(0x5000), ctypes.c_void_p(0x6000), ctypes.c_void_p(0x7000)
+    # lse is required
+    rc = lib.pskv_attn_bwd(ctypes.byref(p), a, a, a, a, a, None, out, None, dout, b, c, d_, None, 0, None)
+    assert rc == pk.PSKV_ERR_INVALID_ARG and "NULL" in pk.pskv_last_error()
+    # a gradient output may not be an input, nor another gradient output
+    rc = lib.pskv_attn_bwd(ctypes.byref(p), a, a, a, a, a, None, out, lse, dout, a, c, d_, None, 0, None)
+    assert rc == pk.PSKV_ERR_INVALID_ARG and "alias" in pk.pskv_last_error()
+    rc = lib.pskv_attn_bwd(ctypes.byref(p), a, a, a, a, a, None, out, lse, dout, b, b, d_, None, 0, None)
+    assert rc == pk.PSKV_ERR_INVALID_ARG and "alias" in pk.pskv_last_error()
+    rc = lib.pskv_attn_bwd(ctypes.byref(p), a, a, a, a, a, None, out, lse, ctypes.c_void_p(0x7004), b, c, d_, None, 0,
+                           None)
+    assert rc == pk.PSKV_ERR_INVALID_ARG and "aligned" in pk.pskv_last_error()
+    m = pk.pskv_multi_params()
+    m.base = p
+    m.Np = 2
+    m.reserved = 0
+    m.kp_stride_n = 0
+    rc = lib.pskv_attn_bwd_multi(ctypes.byref(m), a, a, a, a, a, None, None, out, None, dout, b, c, d_, None, 0, None)
+    assert rc == pk.PSKV_ERR_INVALID_ARG and "NULL" in pk.pskv_last_error()
+    m.reserved = 1
+    rc = lib.pskv_attn_bwd_multi(ctypes.byref(m), a, a, a, a, a, None, None, out, lse, dout, b, c, d_, None, 0, None)
+    assert rc == pk.PSKV_ERR_INVALID_ARG and "reserved" in pk.pskv_last_error()
+    rc = lib.pskv_attn_bwd_multi(None, a, a, a, a, a, None, None, out, lse, dout, b, c, d_, None, 0, None)
+    assert rc == pk.PSKV_ERR_INVALID_ARG
+
+
 def test_multi_params_layout_and_host_validation():
     """The multi-instruction struct is the single-prefix struct plus three fields; its rules are
     checked on the host: B a multiple of Np, Np >= 1, reserved 0, a prefix stride that holds a prefix."""
