@@ -244,6 +244,206 @@ void bwd_dq_mfma_kernel(BwdArgs g, int npasses)
 }
 
 // ------------------------------------------------------------------------------------------
+// dq with the prefix resident in LDS (prefix of at most 256 rows, every 32-row block inside one
+// candidate): the layout of work of the resident forward kernel.  A persistent workgroup copies
+// the prefix K and V of its (instruction, KV head) pair into LDS once; its eight wavefronts
+// then walk independently, without any further workgroup barrier, over the pair's 32-row blocks.
+//
+// Two 8 KB images per 32-key tile serve the three products.  V is kept as row-major fragments
+// (the "K image" layout of pskv_mfma.hpp) for dP^T = V dO^T.  K is kept once, in the
+// transposable layout (the "V image" layout), from which K^T dS^T takes its A fragments through
+// the transposing read; S^T = K Q^T needs row-major K fragments, and the 16 bytes a lane wants
+// for those are two neighbouring 8-byte slots of that same image.  Read that way the lanes of a
+// quarter-wave would hit only a quarter of the banks, so the 16-byte chunks of each 512-byte
+// fragment are stored permuted, chunk p at p ^ (p >> 4) ^ 8u (u: the fragment's 8-key half), which
+// makes both kinds of read conflict-free: lanes pay with one precomputed address per kind.
+// ------------------------------------------------------------------------------------------
+constexpr int kDqMaxTiles = 8;
+
+__global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
+void bwd_dq_resident_kernel(BwdArgs g, int per_vh, int vh_slots, int max_tiles)
+{
+    const Args &a = g.f;
+    extern __shared__ __align__(16) unsigned char smem_generic[];
+    lds_u8 *smem = (lds_u8 *)smem_generic;
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    Ctx X;
+    X.lane = tid & 63;
+    X.h = X.lane >> 5;
+    X.c32 = X.lane & 31;
+    X.Mtot = a.C * a.S * a.G;
+    X.c = a.scale * kLog2e;
+    lds_u8 *vrm = smem;                             // V images, row-major fragments
+    lds_u8 *ktr = smem + max_tiles * kTileBytes;    // K images, transposable, chunks permuted
+    X.k_lane = vrm + X.lane * 16;
+    X.v_lane = ktr + X.lane * 8; // not used for reads (see k_rm and k_tr below)
+    X.scr = smem + 2 * max_tiles * kTileBytes + wave * kScrBytes;
+    X.sv_row_lo = 4 * ((X.c32 >> 4) & 1) + ((X.c32 >> 1) & 3);
+    X.sv_chunk_lo = 2 * ((X.c32 >> 3) & 1) + (X.c32 & 1);
+    // Row-major K fragment of contraction step ks for key c32, half h: logical chunk
+    // 16*hk + 8*(ks%2) + 2*(key%4) + h of fragment (dt = ks/2, j, u); hk, u, j are bits 2, 3, 4 of the key.
+    const int hk = (X.c32 >> 2) & 1, uk = (X.c32 >> 3) & 1, jk = X.c32 >> 4;
+    const int k_rm_common = jk * 1024 + uk * 512 + (16 * hk + 2 * (X.c32 & 3) + (X.h ^ hk)) * 16;
+    lds_u8 *k_rm[2] = {ktr + k_rm_common + 8 * uk * 16, ktr + k_rm_common + 8 * (1 - uk) * 16}; // even ks, odd ks
+    // Transposing read of fragment (dt, j, u): this lane's slot l sits in chunk (l >> 1) ^ (l >> 5) ^ 8u.
+    lds_u8 *k_tr[2] = {ktr + (((X.lane >> 1) ^ X.h) * 16 + (X.lane & 1) * 8),
+                       ktr + (((X.lane >> 1) ^ X.h ^ 8) * 16 + (X.lane & 1) * 8)};
+    const int nblocks = (X.Mtot + kBlockRows - 1) / kBlockRows;
+    const int blk_stride = per_vh * kNW;
+    const int VH = a.Np * a.Hkv;
+    const TileSlot t = make_tile_slot(tid);
+    // the gradient goes out through the forward pass's store routine: dq is laid out like q
+    Args ad = a;
+    ad.out = g.dq;
+    ad.lse = nullptr;
+    ad.o_sb = a.q_sb;
+
+    for (int vh = blockIdx.x % vh_slots; vh < VH; vh += vh_slots) {
+        set_vhead(a, X, vh);
+        const int T = (X.P + kTileKeys - 1) / kTileKeys;
+        __syncthreads(); // every wavefront is done with the images of the virtual head before
+        {
+            uintx4 vk[kDqMaxTiles], kk[kDqMaxTiles];
+            const int last = X.P > 0 ? X.P - 1 : 0;
+#pragma unroll
+            for (int kt = 0; kt < kDqMaxTiles; ++kt)
+                if (kt < T) {
+                    const int kkey = kt * kTileKeys + t.k_row, vkey = kt * kTileKeys + t.v_row;
+                    vk[kt] = ld_global16(X.vpg + (long long)(kkey < X.P ? kkey : last) * a.kp_sp + t.k_chunk * 8);
+                    kk[kt] = ld_global16(X.kpg + (long long)(vkey < X.P ? vkey : last) * a.kp_sp + t.v_chunk * 8);
+                }
+            const int fr = tid >> 5, p5 = tid & 31;
+            const int pos = p5 ^ (p5 >> 4) ^ (8 * (fr & 1));
+#pragma unroll
+            for (int kt = 0; kt < kDqMaxTiles; ++kt)
+                if (kt < T) {
+                    const int kkey = kt * kTileKeys + t.k_row, vkey = kt * kTileKeys + t.v_row;
+                    *(lds_u128 *)(vrm + kt * kTileBytes + tid * 16) = kkey < X.P ? vk[kt] : uintx4{0, 0, 0, 0};
+                    *(lds_u128 *)(ktr + kt * kTileBytes + fr * 512 + pos * 16) = vkey < X.P ? kk[kt] : uintx4{0, 0, 0, 0};
+                }
+        }
+        __syncthreads();
+
+        for (int blk = (blockIdx.x / vh_slots) * kNW + wave; blk < nblocks; blk += blk_stride) {
+            const BlockRows row = decode_block(a, X, blk, X.head, X.cand0);
+            // where the lane's row sits in dq (laid out like q), as store_block_rows wants it
+            BlockRows rowd = row;
+            rowd.o_off = ((unsigned)row.ri * (unsigned)a.q_ss + (unsigned)row.rh * (unsigned)a.q_sh) * 2u;
+            const int i_lo = (int)fdiv(blk * kBlockRows, a.div_g) - (row.b - X.cand0) * a.S;
+            if (i_lo >= row.len) { // nothing but padding
+                store_zero_block_rows(ad, X, rowd);
+                continue;
+            }
+            const int i_hi = (int)fdiv(blk * kBlockRows + kBlockRows - 1, a.div_g) - (row.b - X.cand0) * a.S;
+            const int kmax = i_hi < row.len - 1 ? i_hi : row.len - 1;
+
+            uintx4 q[8], dof[8];
+            load_q_block(a, X, row, q);
+            float drow = 0.f; // <dout_row, out_row>: this lane's 64 columns, then the other half-wave's
+            {
+                const long long obase = (long long)row.b * a.o_sb * 2;
+                const unsigned char *dorow = reinterpret_cast<const unsigned char *>(g.dout) + obase + (row.o_off + 16u * X.h);
+                const unsigned char *orow = reinterpret_cast<const unsigned char *>(a.out) + obase + (row.o_off + 16u * X.h);
+                uintx4 of[8];
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) {
+                    dof[ks] = *reinterpret_cast<const uintx4 *>(dorow + 32 * ks);
+                    of[ks] = *reinterpret_cast<const uintx4 *>(orow + 32 * ks);
+                }
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        drow = __builtin_fmaf(bf16_lo(dof[ks][e]), bf16_lo(of[ks][e]), drow);
+                        drow = __builtin_fmaf(bf16_hi(dof[ks][e]), bf16_hi(of[ks][e]), drow);
+                    }
+                drow += __shfl_xor(drow, 32, 64);
+            }
+            const float lse2 = a.lse[((long long)row.b * a.Hq + row.rh) * a.S + row.ri] * kLog2e;
+
+            floatx16 o[4];
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    o[dt][e] = 0.f;
+
+            // ---- prefix part: every row sees every prefix key ----
+            for (int kt = 0; kt < T; ++kt) {
+                const int to = kt * kTileBytes;
+                floatx16 s, dp;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    s[e] = 0.f;
+                    dp[e] = 0.f;
+                }
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) {
+                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*(lds_u128 *)(k_rm[ks & 1] + to + (ks >> 1) * 2048)),
+                                                                as_bf16x8(q[ks]), s, 0, 0, 0);
+                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(*(lds_u128 *)(X.k_lane + to + ks * 1024)),
+                                                                 as_bf16x8(dof[ks]), dp, 0, 0, 0);
+                }
+                const int nv = X.P - kt * kTileKeys - 4 * X.h; // element e holds key 8*(e/4) + e%4 + 4*h of the tile
+                bf16x8 pf[2];
+                ds_tile(s, dp, X.c, lse2, drow, [&](int e) { return 8 * (e >> 2) + (e & 3) < nv; }, pf);
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int dt = 0; dt < 4; ++dt) {
+                        short4v lo = lds_read_tr(k_tr[0] + to + ((dt * 2 + j) * 2 + 0) * 512);
+                        short4v hi = lds_read_tr(k_tr[1] + to + ((dt * 2 + j) * 2 + 1) * 512);
+                        short8v v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                        bf16x8 kf;
+                        __builtin_memcpy(&kf, &v8, 16);
+                        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, pf[j], o[dt], 0, 0, 0);
+                    }
+            }
+
+            // ---- suffix part: 32-key steps of the block's own candidate ----
+            {
+                Ctx Xs = X; // K and V of the suffix trade places: V in row-major fragments, K through the scratch tile
+                Xs.ksg = X.vsg;
+                Xs.vsg = X.ksg;
+                for (int k0 = 0; k0 <= kmax; k0 += kTileKeys) {
+                    floatx16 s, dp;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        s[e] = 0.f;
+                        dp[e] = 0.f;
+                    }
+                    {
+                        uintx4 kf[8];
+                        load_suffix_k_block(a, X, row.b, k0, kmax, kf);
+#pragma unroll
+                        for (int ks = 0; ks < 8; ++ks)
+                            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[ks]), as_bf16x8(q[ks]), s, 0, 0, 0);
+                    }
+                    {
+                        uintx4 vf[8];
+                        load_suffix_k_block(a, Xs, row.b, k0, kmax, vf); // V rows as row-major fragments
+#pragma unroll
+                        for (int ks = 0; ks < 8; ++ks)
+                            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vf[ks]), as_bf16x8(dof[ks]), dp, 0, 0, 0);
+                    }
+                    uintx4 ktf[2][4];
+                    load_suffix_v_block(a, Xs, row.b, k0, kmax, ktf); // K rows in scratch-image order
+                    // the row sees keys 0..ri of its candidate; element e holds key k0 + 8*(e/4) + e%4 + 4*h
+                    const int lim = row.ri - k0 - 4 * X.h;
+                    bf16x8 pf[2];
+                    ds_tile(s, dp, X.c, lse2, drow, [&](int e) { return 8 * (e >> 2) + (e & 3) <= lim; }, pf);
+                    pv_from_scratch(X, ktf[0], pf[0], o);
+                    pv_from_scratch(X, ktf[1], pf[1], o);
+                }
+            }
+            // store_block_rows divides by the sum of both half-waves' l: 1/(2 * 0.5/scale) = scale
+            store_block_rows(ad, X, rowd, 0.f, 0.5f / a.scale, o);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // dk_suf, dv_suf on the matrix cores.  One wavefront per (candidate, KV head, tile of 32 suffix
 // keys, half DH of the 128 output columns: the accumulators of both halves would not fit the
 // register file); it walks over the candidate's 32-row blocks of stacked query rows (i, g) that can see
@@ -349,6 +549,10 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
         const unsigned short *dob = reinterpret_cast<const unsigned short *>(g.dout) + ob;
         const unsigned short *outb = reinterpret_cast<const unsigned short *>(a.out) + ob;
         const int nrows = len * a.G; // rows (i, g) with i < len, in stacked order i*G + g
+        // the tile's K and V rows as row-major fragments: the same for every block of rows
+        uintx4 kf[8], vf[8];
+        load_suffix_k(a, X, b, k0, kmax, kf);
+        load_suffix_k(a, Xs, b, k0, kmax, vf);
         // the first block that holds a row with i >= k0
         for (int rl0 = (k0 * a.G) / kBlockRows * kBlockRows; rl0 < nrows; rl0 += kBlockRows) {
             // this lane's row of the block, clamped into the candidate
@@ -365,8 +569,7 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
                 dp[e] = 0.f;
             }
             {
-                uintx4 qf[8], kf[8];
-                load_suffix_k(a, X, b, k0, kmax, kf);
+                uintx4 qf[8];
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks)
                     qf[ks] = ld_global16(qb + qoff + 16 * ks);
@@ -376,8 +579,7 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
             }
             float drow = 0.f;
             {
-                uintx4 dof[8], vf[8];
-                load_suffix_k(a, Xs, b, k0, kmax, vf);
+                uintx4 dof[8];
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks)
                     dof[ks] = ld_global16(dob + ooff + 16 * ks);
@@ -498,12 +700,33 @@ hipError_t launch_bwd_dq_mfma(const BwdArgs &g, hipStream_t stream)
         if (e == hipSuccess)
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(bwd_dq_mfma_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kBwdLdsBytes);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(bwd_dq_resident_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    2 * kDqMaxTiles * kTileBytes + kNW * kScrBytes);
         if (e != hipSuccess)
             return e;
         num_cu = n > 0 ? n : 256;
     }
     const Args &a = g.f;
     const long long rows = (long long)a.C * a.S * a.G;
+    // Short prefixes stay resident in LDS (the split of the workgroups over the (instruction, KV
+    // head) pairs is that of the resident forward kernel).
+    if (a.P <= kDqMaxTiles * kTileKeys && rows % kBlockRows == 0 && ((long long)a.S * a.G) % kBlockRows == 0 &&
+        block_offsets_fit(a)) {
+        const int max_tiles = (a.P + kTileKeys - 1) / kTileKeys;
+        const long long nblocks = rows / kBlockRows;
+        const long long VH = (long long)a.Np * a.Hkv;
+        const long long vh_slots = VH < num_cu ? VH : num_cu;
+        long long per_vh = num_cu / vh_slots;
+        const long long useful = (nblocks + kNW - 1) / kNW;
+        if (per_vh > useful)
+            per_vh = useful;
+        const size_t lds = (size_t)2 * max_tiles * kTileBytes + kNW * kScrBytes;
+        hipLaunchKernelGGL(bwd_dq_resident_kernel, dim3((unsigned)(per_vh * vh_slots)), dim3(kNW * 64), lds, stream, g,
+                           (int)per_vh, (int)vh_slots, max_tiles);
+        return hipGetLastError();
+    }
     const long long npasses = ((rows + kBwdPassRows - 1) / kBwdPassRows) * a.Np * a.Hkv;
     // two workgroups fit a compute unit's LDS; registers allow one, so one per compute unit
     const unsigned grid = (unsigned)(npasses < num_cu ? npasses : num_cu);
