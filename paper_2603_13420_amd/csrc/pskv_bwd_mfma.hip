@@ -18,6 +18,7 @@
 // layout the transposing read wants.  The suffix rows of the block's own candidate(s) follow,
 // with K/V fragments straight from global memory and K^T through the per-wave scratch tile.
 // No running maximum is needed: lse comes from the forward pass, every weight is at most one.
+// A second kernel further down keeps short prefixes resident in LDS instead of streaming them.
 #include "pskv_mfma.hpp"
 
 namespace pskv {

@@ -64,7 +64,8 @@ size_t bwd_simple_lds_bytes(const Args &a, int dtype);
 size_t bwd_dkv_lds_bytes(const Args &a, int dtype);
 hipError_t launch_bwd_dq_simple(const BwdArgs &g, int dtype, hipStream_t stream);
 hipError_t launch_bwd_dkv_simple(const BwdArgs &g, int dtype, hipStream_t stream);
-// Matrix-core kernel for dq: bf16, D == 128, single shared prefix.
+// Matrix-core kernels for dq and for dk/dv: bf16, D == 128 (prefixes of up to 256 rows stay resident
+// in LDS for dq, longer ones are streamed).
 bool bwd_mfma_supported(const Args &a, int dtype);
 hipError_t launch_bwd_dq_mfma(const BwdArgs &g, hipStream_t stream);
 hipError_t launch_bwd_dkv_mfma(const BwdArgs &g, hipStream_t stream);
