@@ -130,13 +130,15 @@ def bench_backward(args):
         out = pk.pskv_attn_fwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], lse=lse,
                                scale=inp.scale)
         sets.append(dict(d, out=out, lse=lse, dout=dout0.clone(), dq=torch.empty_like(d["q"]),
-                         dk=torch.empty_like(d["k_suf"]), dv=torch.empty_like(d["k_suf"])))
+                         dk=torch.empty_like(d["k_suf"]), dv=torch.empty_like(d["k_suf"]),
+                         ws=torch.empty(w.B * w.Hq * w.S * 4, dtype=torch.uint8, device="cuda:0")))
     torch.cuda.synchronize()
 
     def call(i):
         d = sets[i]
         pk.pskv_attn_bwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], d["out"], d["lse"],
-                         d["dout"], dq=d["dq"], dk_suf=d["dk"], dv_suf=d["dv"], impl=args.impl, scale=inp.scale)
+                         d["dout"], dq=d["dq"], dk_suf=d["dk"], dv_suf=d["dv"], impl=args.impl, scale=inp.scale,
+                         workspace=d["ws"])
 
     steps, warmup = min(args.steps, 400), min(args.warmup, 100)
     for i in range(warmup):

@@ -204,11 +204,20 @@ pskv_status pskv_attn_fwd_multi(const pskv_multi_params *p,
  *   dq    [B,S,Hq,D]  device, written in full, laid out like q (q_stride_*); padded rows = 0
  *   dk_suf, dv_suf [B,S,Hkv,D] device, written in full, laid out like k_suf; padded rows = 0
  *
+ *   workspace           optional device scratch of the caller's, 16-byte aligned, not aliasing any
+ *                       other argument.  With at least pskv_attn_bwd_workspace_bytes(p) bytes the
+ *                       matrix-core kernels pass <dout_row, out_row> of every row from the first
+ *                       kernel to the second through it, so that `out` is read once; with NULL or
+ *                       fewer bytes the call works all the same and reads `out` twice.  Its
+ *                       contents after the call are unspecified.
+ *
  * Padded rows of dout are ignored.  Same ownership, stream and error rules as the forward call;
  * outputs must not alias inputs or one another.  p->impl: SIMPLE selects the vector-ALU kernels
  * (fp64 arithmetic for f32 tensors, fp32 for bf16); AUTO uses the matrix-core kernels when the
  * tensors are bf16 with D == 128; MFMA insists on that and is refused otherwise.
  */
+size_t pskv_attn_bwd_workspace_bytes(const pskv_attn_params *p); /* B*Hq*S*4; (size_t)-1 for invalid params */
+
 pskv_status pskv_attn_bwd(const pskv_attn_params *p,
                           const void *q, const void *k_suf, const void *v_suf,
                           const void *k_pre, const void *v_pre,
@@ -225,7 +234,7 @@ pskv_status pskv_attn_bwd(const pskv_attn_params *p,
  * (the last pre_len[n] of the P left-padded ones, App. F.1).  Prefixes get no gradient.
  *
  *   k_pre, v_pre, pre_len   as for pskv_attn_fwd_multi (same params struct)
- *   everything else         as for pskv_attn_bwd
+ *   everything else         as for pskv_attn_bwd (workspace: pskv_attn_bwd_workspace_bytes(&p->base))
  *
  * With Np == 1 and pre_len == NULL this is pskv_attn_bwd.
  */

@@ -19,7 +19,8 @@ _IMPL = {"auto": PSKV_IMPL_AUTO, "simple": PSKV_IMPL_SIMPLE, "mfma": PSKV_IMPL_M
 
 EXPORTS = ["pskv_version", "pskv_status_str", "pskv_last_error", "pskv_attn_fwd_workspace_bytes",
            "pskv_attn_validate", "pskv_attn_fwd", "pskv_attn_fwd_timed",
-           "pskv_attn_multi_validate", "pskv_attn_fwd_multi", "pskv_attn_bwd", "pskv_attn_bwd_multi"]
+           "pskv_attn_multi_validate", "pskv_attn_fwd_multi", "pskv_attn_bwd", "pskv_attn_bwd_multi",
+           "pskv_attn_bwd_workspace_bytes"]
 
 
 class pskv_attn_params(ctypes.Structure):
@@ -77,6 +78,8 @@ def load():
     lib.pskv_attn_fwd_multi.argtypes = [PM, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.pskv_attn_bwd.restype = ctypes.c_int
     lib.pskv_attn_bwd.argtypes = [P] + [vp] * 13 + [ctypes.c_size_t, vp]
+    lib.pskv_attn_bwd_workspace_bytes.restype = ctypes.c_size_t
+    lib.pskv_attn_bwd_workspace_bytes.argtypes = [P]
     lib.pskv_attn_bwd_multi.restype = ctypes.c_int
     lib.pskv_attn_bwd_multi.argtypes = [PM] + [vp] * 14 + [ctypes.c_size_t, vp]
     _lib = lib
@@ -303,11 +306,26 @@ class PreparedMultiCall:
             _raise(rc)
 
 
+def _bwd_workspace(p, workspace, device):
+    """The scratch tensor to hand to a backward call: the caller's, or a fresh one from torch
+    (workspace=None), or none at all (workspace=False)."""
+    import torch
+    if workspace is False:
+        return None, 0
+    if workspace is None:
+        need = int(load().pskv_attn_bwd_workspace_bytes(ctypes.byref(p)))
+        if need >= 1 << 62:      # invalid parameters: the call itself reports what is wrong
+            return None, 0
+        workspace = torch.empty(need, dtype=torch.uint8, device=device)
+    return workspace, workspace.numel() * workspace.element_size()
+
+
 def pskv_attn_bwd(q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse, dout, dq=None, dk_suf=None, dv_suf=None,
-                  impl: str = "auto", scale: float = 0.0, stream: Optional[int] = None):
+                  impl: str = "auto", scale: float = 0.0, stream: Optional[int] = None, workspace=None):
     """Enqueue the backward pass (gradients with respect to q, k_suf, v_suf; the prefix is a
     constant).  out and lse are the forward results; dout is laid out like out.  Gradient
-    tensors are allocated by torch when not given (dq like q, dk_suf/dv_suf like k_suf).
+    tensors are allocated by torch when not given (dq like q, dk_suf/dv_suf like k_suf), and so is
+    the scratch tensor (workspace: a tensor to use instead, or False for a call without scratch).
     Returns (dq, dk_suf, dv_suf)."""
     import torch
     if lse is None:
@@ -324,19 +342,21 @@ def pskv_attn_bwd(q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse, dout, dq=Non
         if t.shape != k_suf.shape or t.stride() != k_suf.stride() or t.dtype != q.dtype:
             raise ValueError(f"{name} must have the shape, strides and dtype of k_suf")
     p = _params_from_tensors(q, k_suf, k_pre, out, impl, scale)
+    ws, ws_bytes = _bwd_workspace(p, workspace, q.device)
     if stream is None:
         stream = torch.cuda.current_stream(q.device).cuda_stream
     with torch.cuda.device(q.device):
         rc = load().pskv_attn_bwd(ctypes.byref(p), _ptr(q), _ptr(k_suf), _ptr(v_suf), _ptr(k_pre), _ptr(v_pre),
                                   _ptr(suf_len), _ptr(out), _ptr(lse), _ptr(dout), _ptr(dq), _ptr(dk_suf),
-                                  _ptr(dv_suf), None, 0, ctypes.c_void_p(stream))
+                                  _ptr(dv_suf), _ptr(ws), ws_bytes, ctypes.c_void_p(stream))
     if rc != PSKV_OK:
         _raise(rc)
     return dq, dk_suf, dv_suf
 
 
 def pskv_attn_bwd_multi(q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, out, lse, dout, dq=None, dk_suf=None,
-                        dv_suf=None, impl: str = "auto", scale: float = 0.0, stream: Optional[int] = None):
+                        dv_suf=None, impl: str = "auto", scale: float = 0.0, stream: Optional[int] = None,
+                        workspace=None):
     """Backward pass of the batched multi-instruction form (arguments as for pskv_attn_fwd_multi
     and pskv_attn_bwd).  Returns (dq, dk_suf, dv_suf)."""
     import torch
@@ -353,12 +373,13 @@ def pskv_attn_bwd_multi(q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, out, ls
     for name, t in (("dk_suf", dk_suf), ("dv_suf", dv_suf)):
         if t.shape != k_suf.shape or t.stride() != k_suf.stride() or t.dtype != q.dtype:
             raise ValueError(f"{name} must have the shape, strides and dtype of k_suf")
+    ws, ws_bytes = _bwd_workspace(p.base, workspace, q.device)
     if stream is None:
         stream = torch.cuda.current_stream(q.device).cuda_stream
     with torch.cuda.device(q.device):
         rc = load().pskv_attn_bwd_multi(ctypes.byref(p), _ptr(q), _ptr(k_suf), _ptr(v_suf), _ptr(k_pre), _ptr(v_pre),
                                         _ptr(pre_len), _ptr(suf_len), _ptr(out), _ptr(lse), _ptr(dout), _ptr(dq),
-                                        _ptr(dk_suf), _ptr(dv_suf), None, 0, ctypes.c_void_p(stream))
+                                        _ptr(dk_suf), _ptr(dv_suf), _ptr(ws), ws_bytes, ctypes.c_void_p(stream))
     if rc != PSKV_OK:
         _raise(rc)
     return dq, dk_suf, dv_suf

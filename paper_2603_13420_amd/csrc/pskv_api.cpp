@@ -175,6 +175,15 @@ size_t pskv_attn_fwd_workspace_bytes(const pskv_attn_params *p)
     return 0; // every path is fully fused
 }
 
+size_t pskv_attn_bwd_workspace_bytes(const pskv_attn_params *p)
+{
+    pskv::Args a{};
+    bool use_mfma = false;
+    if (resolve(p, 1, 0, a, use_mfma) != PSKV_OK)
+        return (size_t)-1;
+    return (size_t)p->B * (size_t)p->Hq * (size_t)p->S * sizeof(float);
+}
+
 pskv_status pskv_attn_validate(const pskv_attn_params *p)
 {
     pskv::Args a{};
@@ -229,7 +238,7 @@ pskv_status pskv_attn_fwd_multi(const pskv_multi_params *p, const void *q, const
 static pskv_status launch_bwd(const pskv_attn_params *p, int np, int64_t kp_stride_n, const void *q, const void *k_suf,
                               const void *v_suf, const void *k_pre, const void *v_pre, const int32_t *pre_len,
                               const int32_t *suf_len, const void *out, const float *lse, const void *dout, void *dq,
-                              void *dk_suf, void *dv_suf, void *hip_stream)
+                              void *dk_suf, void *dv_suf, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     pskv::BwdArgs g{};
     pskv::Args &a = g.f;
@@ -273,6 +282,21 @@ static pskv_status launch_bwd(const pskv_attn_params *p, int np, int64_t kp_stri
     a.out = const_cast<void *>(out); // read-only in every backward kernel
     a.lse = const_cast<float *>(lse);
     g.dout = dout; g.dq = dq; g.dk = dk_suf; g.dv = dv_suf;
+    // With enough workspace the matrix-core kernels pass <dout_row, out_row> from the first kernel
+    // to the second through it; without, the second reads out again.
+    const size_t delta_bytes = (size_t)p->B * (size_t)p->Hq * (size_t)p->S * sizeof(float);
+    g.delta = nullptr;
+    if (dq_mfma && workspace && workspace_bytes >= delta_bytes) {
+        if (reinterpret_cast<uintptr_t>(workspace) & 15u)
+            return fail(PSKV_ERR_INVALID_ARG, "workspace %p is not 16-byte aligned", workspace);
+        for (const void *in : ins)
+            if (workspace == in)
+                return fail(PSKV_ERR_INVALID_ARG, "workspace must not alias an input");
+        for (void *o : outs)
+            if (workspace == o)
+                return fail(PSKV_ERR_INVALID_ARG, "workspace must not alias an output");
+        g.delta = static_cast<float *>(workspace);
+    }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipError_t e = dq_mfma ? pskv::launch_bwd_dq_mfma(g, stream) : pskv::launch_bwd_dq_simple(g, p->dtype, stream);
     if (e == hipSuccess)
@@ -288,10 +312,8 @@ pskv_status pskv_attn_bwd(const pskv_attn_params *p, const void *q, const void *
                           const float *lse, const void *dout, void *dq, void *dk_suf, void *dv_suf,
                           void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    (void)workspace;
-    (void)workspace_bytes; // no path needs scratch
     return launch_bwd(p, 1, 0, q, k_suf, v_suf, k_pre, v_pre, nullptr, suf_len, out, lse, dout, dq, dk_suf, dv_suf,
-                      hip_stream);
+                      workspace, workspace_bytes, hip_stream);
 }
 
 pskv_status pskv_attn_bwd_multi(const pskv_multi_params *p, const void *q, const void *k_suf, const void *v_suf,
@@ -299,14 +321,12 @@ pskv_status pskv_attn_bwd_multi(const pskv_multi_params *p, const void *q, const
                                 const void *out, const float *lse, const void *dout, void *dq, void *dk_suf,
                                 void *dv_suf, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    (void)workspace;
-    (void)workspace_bytes; // no path needs scratch
     if (!p)
         return fail(PSKV_ERR_INVALID_ARG, "params is NULL");
     if (p->reserved != 0)
         return fail(PSKV_ERR_INVALID_ARG, "reserved field must be 0");
     return launch_bwd(&p->base, p->Np, p->kp_stride_n, q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, out, lse, dout, dq,
-                      dk_suf, dv_suf, hip_stream);
+                      dk_suf, dv_suf, workspace, workspace_bytes, hip_stream);
 }
 
 pskv_status pskv_attn_fwd_timed(const pskv_attn_params *p, const void *q, const void *k_suf,

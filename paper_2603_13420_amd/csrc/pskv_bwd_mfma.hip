@@ -122,6 +122,8 @@ void bwd_dq_mfma_kernel(BwdArgs g, int npasses)
                 }
             drow += __shfl_xor(drow, 32, 64);
         }
+        if (g.delta && active && row.rin && X.h == 0)
+            g.delta[((long long)row.rb * a.Hq + row.rh) * a.S + row.ri] = drow;
         const float lse2 = (row.rin ? a.lse[((long long)row.rb * a.Hq + row.rh) * a.S + row.ri] : 0.f) * kLog2e;
 
         floatx16 o[4];
@@ -361,6 +363,8 @@ void bwd_dq_resident_kernel(BwdArgs g, int per_vh, int vh_slots, int max_tiles)
                     }
                 drow += __shfl_xor(drow, 32, 64);
             }
+            if (g.delta && X.h == 0)
+                g.delta[((long long)row.b * a.Hq + row.rh) * a.S + row.ri] = drow;
             const float lse2 = a.lse[((long long)row.b * a.Hq + row.rh) * a.S + row.ri] * kLog2e;
 
             floatx16 o[4];
@@ -488,7 +492,43 @@ __device__ inline void pv_half_from_scratch(const Ctx &X, const uintx4 (&vstep)[
         o[i2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i2], pfj, o[i2], 0, 0, 0);
 }
 
+// The same accumulation for the 16-row step j of a 32-row block whose rows the lanes already hold
+// as row-major fragments (lane (row c32, half h): columns 16*ks + 8*h ..+7 in frag[ks - 4*DH] for the
+// four ks of this half of the columns): the lanes that own rows of step j put their chunks where
+// the scratch image wants them - chunk (row r, columns 16*ks + 8*h) belongs to fragment
+// (dt = ks/2, u = (r/8)%2), slot pair 16*((r/4)%2) + 8*(ks%2) + 2*(r%4) + h - and the transposing
+// read hands them back as A fragments.
 template <int DH>
+__device__ inline void pv_half_from_fragments(const Ctx &X, const uintx4 (&frag)[4], int j, bf16x8 pfj, floatx16 (&o)[2])
+{
+    if ((X.c32 >> 4) == j) {
+        const int u = (X.c32 >> 3) & 1;
+        lds_u8 *dst = X.scr + u * 512 + (16 * ((X.c32 >> 2) & 1) + 2 * (X.c32 & 3) + X.h) * 16;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int ks = 4 * DH + i;
+            *(lds_u128 *)(dst + (ks >> 1) * 1024 + (ks & 1) * 128) = frag[i];
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    bf16x8 va[2];
+#pragma unroll
+    for (int i2 = 0; i2 < 2; ++i2) {
+        const int dt = 2 * DH + i2;
+        short4v lo = lds_read_tr(X.scr + X.lane * 8 + (dt * 2 + 0) * 512);
+        short4v hi = lds_read_tr(X.scr + X.lane * 8 + (dt * 2 + 1) * 512);
+        short8v v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        __builtin_memcpy(&va[i2], &v8, 16);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int i2 = 0; i2 < 2; ++i2)
+        o[i2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i2], pfj, o[i2], 0, 0, 0);
+}
+
+template <int DH, bool HAS_DELTA>
 __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, lds_u8 *smem, int tid, int wave, int unit,
                                                             int nkt)
 {
@@ -569,34 +609,41 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
                 s[e] = 0.f;
                 dp[e] = 0.f;
             }
+            // everything the block needs from global memory is requested here, in one round trip
+            uintx4 qh[4], doh[4]; // this half's columns of q and dout, kept for the second products
+            float drow = 0.f;
             {
-                uintx4 qf[8];
+                uintx4 qf[8], dof[8], of[HAS_DELTA ? 1 : 8];
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
+                for (int ks = 0; ks < 8; ++ks) {
                     qf[ks] = ld_global16(qb + qoff + 16 * ks);
+                    dof[ks] = ld_global16(dob + ooff + 16 * ks);
+                    if constexpr (!HAS_DELTA)
+                        of[ks] = ld_global16(outb + ooff + 16 * ks);
+                }
+                if constexpr (HAS_DELTA) // left there by the dq kernel (the clamped row is a valid one, hence written)
+                    drow = g.delta[((long long)b * a.Hq + k * a.G + gq) * a.S + ri];
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks)
                     s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qf[ks]), as_bf16x8(kf[ks]), s, 0, 0, 0);
-            }
-            float drow = 0.f;
-            {
-                uintx4 dof[8];
-#pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
-                    dof[ks] = ld_global16(dob + ooff + 16 * ks);
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks)
                     dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(dof[ks]), as_bf16x8(vf[ks]), dp, 0, 0, 0);
+                if constexpr (!HAS_DELTA) {
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks) {
-                    const uintx4 of = ld_global16(outb + ooff + 16 * ks);
+                    for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        drow = __builtin_fmaf(bf16_lo(dof[ks][e]), bf16_lo(of[e]), drow);
-                        drow = __builtin_fmaf(bf16_hi(dof[ks][e]), bf16_hi(of[e]), drow);
-                    }
+                        for (int e = 0; e < 4; ++e) {
+                            drow = __builtin_fmaf(bf16_lo(dof[ks][e]), bf16_lo(of[ks][e]), drow);
+                            drow = __builtin_fmaf(bf16_hi(dof[ks][e]), bf16_hi(of[ks][e]), drow);
+                        }
+                    drow += __shfl_xor(drow, 32, 64);
                 }
-                drow += __shfl_xor(drow, 32, 64);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    qh[i] = qf[4 * DH + i];
+                    doh[i] = dof[4 * DH + i];
+                }
             }
             // row quantities to LDS, then each lane fetches those of the 16 rows its elements belong to
             if (X.h == 0) {
@@ -634,19 +681,8 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
             // dO^T and Q^T of the block through the scratch tile, 16 rows at a time
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                uintx4 dst2[2], qst2[2];
-#pragma unroll
-                for (int i2 = 0; i2 < 2; ++i2) {
-                    const int frag = 2 * (2 * DH + i2) + X.h; // fragment (dt = frag >> 1, u = frag & 1)
-                    int rb2 = rl0 + 16 * j + 8 * (frag & 1) + X.sv_row_lo;
-                    rb2 = rb2 < nrows ? rb2 : nrows - 1;
-                    const int ir = (int)fdiv((unsigned)rb2, a.div_g), g2 = rb2 - ir * a.G;
-                    const int ch = (4 * (frag >> 1) + X.sv_chunk_lo) * 8;
-                    dst2[i2] = ld_global16(dob + (long long)ir * a.o_ss + (long long)g2 * a.o_sh + ch);
-                    qst2[i2] = ld_global16(qb + (long long)ir * a.q_ss + (long long)g2 * a.q_sh + ch);
-                }
-                pv_half_from_scratch<DH>(X, dst2, pfp[j], dv);
-                pv_half_from_scratch<DH>(X, qst2, pfs[j], dk);
+                pv_half_from_fragments<DH>(X, doh, j, pfp[j], dv);
+                pv_half_from_fragments<DH>(X, qh, j, pfs[j], dk);
             }
         }
     }
@@ -657,6 +693,7 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
     store_rows<DH, DH>(X, dst_v, dst_ok, kvalid, 1.0f, dv4);
 }
 
+template <bool HAS_DELTA>
 __global__ __attribute__((amdgpu_flat_work_group_size(256, 256), amdgpu_waves_per_eu(2, 2)))
 void bwd_dkv_mfma_kernel(BwdArgs g, int nunits, int nkt)
 {
@@ -668,9 +705,9 @@ void bwd_dkv_mfma_kernel(BwdArgs g, int nunits, int nkt)
     if (unit2 >= 2 * nunits) // no workgroup barrier anywhere in this kernel
         return;
     if (unit2 & 1)
-        bwd_dkv_unit<1>(g, smem, tid, wave, unit2 >> 1, nkt);
+        bwd_dkv_unit<1, HAS_DELTA>(g, smem, tid, wave, unit2 >> 1, nkt);
     else
-        bwd_dkv_unit<0>(g, smem, tid, wave, unit2 >> 1, nkt);
+        bwd_dkv_unit<0, HAS_DELTA>(g, smem, tid, wave, unit2 >> 1, nkt);
 }
 
 } // namespace
@@ -686,7 +723,12 @@ hipError_t launch_bwd_dkv_mfma(const BwdArgs &g, hipStream_t stream)
     const int nkt = (a.S + kTileKeys - 1) / kTileKeys;
     const long long nunits = (long long)a.B * a.Hkv * nkt;
     const unsigned grid = (unsigned)((2 * nunits + kDkvWaves - 1) / kDkvWaves);
-    hipLaunchKernelGGL(bwd_dkv_mfma_kernel, dim3(grid), dim3(kDkvWaves * 64), kDkvLdsBytes, stream, g, (int)nunits, nkt);
+    if (g.delta)
+        hipLaunchKernelGGL(bwd_dkv_mfma_kernel<true>, dim3(grid), dim3(kDkvWaves * 64), kDkvLdsBytes, stream, g, (int)nunits,
+                           nkt);
+    else
+        hipLaunchKernelGGL(bwd_dkv_mfma_kernel<false>, dim3(grid), dim3(kDkvWaves * 64), kDkvLdsBytes, stream, g, (int)nunits,
+                           nkt);
     return hipGetLastError();
 }
 

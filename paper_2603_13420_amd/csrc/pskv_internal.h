@@ -59,6 +59,10 @@ struct BwdArgs {
     Args f;
     const void *dout;
     void *dq, *dk, *dv;
+    // Optional [B,Hq,S] floats (laid out like lse) in the caller's workspace: the matrix-core dq
+    // kernels leave <dout_row, out_row> of every row they process there and the dk/dv kernel, which
+    // runs after them on the same stream, takes it from there instead of reading out again.
+    float *delta;
 };
 size_t bwd_simple_lds_bytes(const Args &a, int dtype);
 size_t bwd_dkv_lds_bytes(const Args &a, int dtype);

@@ -137,6 +137,14 @@ def test_bwd_refuses_bad_pointers_before_any_launch():
     assert rc == pk.PSKV_ERR_INVALID_ARG
 
 
+def test_bwd_workspace_size():
+    lib = pk.load()
+    p = ok(B=7, S=24, Hq=32, Hkv=8, D=128, dtype="bf16")
+    assert lib.pskv_attn_bwd_workspace_bytes(ctypes.byref(p)) == 7 * 32 * 24 * 4
+    p.D = 0
+    assert lib.pskv_attn_bwd_workspace_bytes(ctypes.byref(p)) == ctypes.c_size_t(-1).value
+
+
 def test_multi_params_layout_and_host_validation():
     """The multi-instruction struct is the single-prefix struct plus three fields; its rules are
     checked on the host: B a multiple of Np, Np >= 1, reserved 0, a prefix stride that holds a prefix."""

@@ -125,3 +125,25 @@ def test_bwd_refuses_missing_lse_wrong_path_and_aliases(pk):
         pk.pskv_attn_bwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], out, lse,
                          torch.ones_like(out), dq=d["q"])
     assert e.value.status == pk.PSKV_ERR_INVALID_ARG
+
+
+def test_bwd_without_workspace_gives_the_same_bits(pk):
+    """The scratch tensor only saves a second read of out: with and without it the gradients
+    are the same bits (the same sum <dout,out> is formed in the same order either way)."""
+    import torch
+    w = gen.custom_workload("bwd_ws", 6, 256, 24, 16, 24, 8, 2, 128, "bf16", index=870)
+    inp = gen.make_inputs(w, pad="nan")
+    d = pu.to_device(inp)
+    lse = torch.empty((w.B, w.Hq, w.S), dtype=torch.float32, device="cuda:0")
+    out = pk.pskv_attn_fwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], lse=lse, scale=inp.scale)
+    dout_host, _ = make_dout(inp, 871)
+    dout = torch.from_numpy(dout_host).view(torch.bfloat16).to("cuda:0")
+    args = (d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], out, lse, dout)
+    with_ws = pk.pskv_attn_bwd(*args, scale=inp.scale)
+    small = torch.empty(16, dtype=torch.uint8, device="cuda:0")     # too small: ignored
+    without = pk.pskv_attn_bwd(*args, scale=inp.scale, workspace=False)
+    too_small = pk.pskv_attn_bwd(*args, scale=inp.scale, workspace=small)
+    torch.cuda.synchronize()
+    for x, y, z in zip(with_ws, without, too_small):
+        assert torch.equal(x.view(torch.int16), y.view(torch.int16))
+        assert torch.equal(x.view(torch.int16), z.view(torch.int16))
