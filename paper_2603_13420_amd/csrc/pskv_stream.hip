@@ -560,8 +560,15 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
             g.vs = reinterpret_cast<const unsigned char *>(X.vsg + (long long)ps.b * a.ks_sb);
         }
         const int r0 = ps.blk * kBlockRows;
-        const bool active = ps.active;
         const Row row = nxt;
+        // This wavefront's own share of the pass's tiles: the prefix and the suffix tiles up to the
+        // last key its own block sees (Tw <= T); none at all if it has no block or its block holds
+        // nothing but padding (then it only stores zeros).
+        const int cblk = ps.blk - (ps.b - ps.cand0) * cs.nblk_c; // block within the candidate
+        const int i_lo_w = (int)fdiv(cblk * kBlockRows, a.div_g);
+        const int i_hi_w = (int)fdiv(cblk * kBlockRows + kBlockRows - 1, a.div_g);
+        const bool active = ps.active && i_lo_w < len;
+        const int Tw = Tp + (i_hi_w < skmax ? i_hi_w : skmax) / kTileKeys + 1;
         const bool rvalid = active && row.rin && (int)row.ri < clamp_len(a, row.rlen);
 
         // The ring is free here (the barrier that ended the previous pass).  Tiles 0..3 go in at once.
@@ -590,6 +597,31 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
         auto lim_of = [&](int t) { return t >= Tp ? lim_suffix - t * kTileKeys : (t == Tp - 1 ? lim_last_prefix : 1 << 20); };
         const int tm = X.P / kTileKeys; // first tile with keys that some row does not see (>= 2)
 
+        // A wavefront without a block (the last pass of a unit may hold fewer than eight) takes part
+        // in the staging and in the barriers only, and leaves the matrix cores of its SIMD to its
+        // neighbour: same barriers, in the same order, as the path below.
+        if (!active) {
+            if (ps.active)
+                store_zero_block(a, X, row);
+            for (int t = 2; t + 1 <= T - 2; t += 2) {
+                stage_write(t + 2, kv0, vv0);
+                stage_write(t + 3, kv1, vv1);
+                cand_stage_load(g, t + 4, kv0, vv0);
+                cand_stage_load(g, t + 5, kv1, vv1);
+                __syncthreads();
+            }
+            p += gridDim.x;
+            ps = make_cand_pass(a, cs, p, npasses, wave);
+            nxt = decode_row(a, X, ps.blk, ps.head, ps.cand0);
+            load_q(a, X, nxt, q);
+            if (X.lane == 0)
+                *(lds_int *)X.scr = 0;
+            __syncthreads(); // ends the pass
+            wg_bad |= __builtin_amdgcn_ballot_w64(*(lds_int *)(smem + kRing * kSlotBytes + (X.lane & (kNW - 1)) * kScrBytes) !=
+                                                  0) != 0;
+            continue;
+        }
+
         // ---- first prefix tile: scores, reference maximum ----
         floatx16 sA, sB;
 #pragma unroll
@@ -615,7 +647,7 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
 
         pipe_tile<true, false, false, false, false, true, true>(kimg(1), nokf, vimg(0), kimg(2), vimg(0), pre, q, sA, sB,
                                                                 X.c, m, 0, l, pA, pA, o);
-        pipe_tile<true, false, true, true, false, true, true>(kimg(2), nokf, vimg(0), kimg(3 < T ? 3 : T - 1), vimg(1), pre, q,
+        pipe_tile<true, false, true, true, false, true, true>(kimg(2), nokf, vimg(0), kimg(3 < Tw ? 3 : Tw - 1), vimg(1), pre, q,
                                                               sB, sA, X.c, m, 0, l, pA, pB, o);
 #define PSKV_CAND_PAIR(t, MASKED)                                                                                      \
     do {                                                                                                               \
@@ -623,12 +655,12 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
                                                                 vimg(t), pre, q, sA, sB, X.c, m, lim_of(t), l, pB, pA, \
                                                                 o);                                                    \
         pipe_tile<true, false, true, false, MASKED, true, true>(kimg((t) + 2), nokf, vimg(t),                          \
-                                                                kimg((t) + 3 < T ? (t) + 3 : T - 1), vimg((t) + 1),    \
+                                                                kimg((t) + 3 < Tw ? (t) + 3 : Tw - 1), vimg((t) + 1),  \
                                                                 pre, q, sB, sA, X.c, m, lim_of((t) + 1), l, pA, pB,    \
                                                                 o);                                                    \
     } while (0)
         int t = 2;
-        for (; t + 1 <= T - 2 && t + 1 < tm; t += 2) { // pairs of fully visible tiles
+        for (; t + 1 <= Tw - 2 && t + 1 < tm; t += 2) { // pairs of fully visible tiles
             stage_write(t + 2, kv0, vv0);
             stage_write(t + 3, kv1, vv1);
             cand_stage_load(g, t + 4, kv0, vv0);
@@ -636,7 +668,7 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
             __syncthreads();
             PSKV_CAND_PAIR(t, false);
         }
-        for (; t + 1 <= T - 2; t += 2) {
+        for (; t + 1 <= Tw - 2; t += 2) {
             stage_write(t + 2, kv0, vv0);
             stage_write(t + 3, kv1, vv1);
             cand_stage_load(g, t + 4, kv0, vv0);
@@ -644,9 +676,10 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
             __syncthreads();
             PSKV_CAND_PAIR(t, true);
         }
+        const int t_own = t; // the wavefront's own tiles end here; staging for the others goes on below
 #undef PSKV_CAND_PAIR
-        if (t <= T - 2) { // one step left over: do it and put scores and weights back in their places
-            pipe_tile<true, false, true, false, true, false, true>(kimg(t + 1), nokf, vimg(t - 1), kimg(T - 1), vimg(t), pre,
+        if (t <= Tw - 2) { // one step left over: do it and put scores and weights back in their places
+            pipe_tile<true, false, true, false, true, false, true>(kimg(t + 1), nokf, vimg(t - 1), kimg(Tw - 1), vimg(t), pre,
                                                                    q, sA, sB, X.c, m, lim_of(t), l, pB, pA, o);
             sA = sB;
             pB[0] = pA[0];
@@ -660,13 +693,21 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
         load_q(a, X, nxt, q);
 
         // ---- last tile: its weights under the value product of the tile before, then its own ----
-        pipe_tile<false, false, true, false, true, false, false>(kimg(0), nokf, vimg(T - 2), kimg(0), vimg(0), pre, q, sA, sA,
-                                                                 X.c, m, lim_of(T - 1), l, pB, pA, o);
-        pv_tile(vimg(T - 1), pA, o);
+        pipe_tile<false, false, true, false, true, false, false>(kimg(0), nokf, vimg(Tw - 2), kimg(0), vimg(0), pre, q, sA, sA,
+                                                                 X.c, m, lim_of(Tw - 1), l, pB, pA, o);
+        pv_tile(vimg(Tw - 1), pA, o);
 
         const bool bad = __builtin_amdgcn_ballot_w64(rvalid && !(l < kBig)) != 0;
-        if (active)
-            store_block(a, X, r0, row, rvalid, m, l, o);
+        // the rest of the pass's staging, for the wavefronts whose blocks see further (before this
+        // wavefront's store: they are the ones the pass is waiting for)
+        for (t = t_own; t + 1 <= T - 2; t += 2) {
+            stage_write(t + 2, kv0, vv0);
+            stage_write(t + 3, kv1, vv1);
+            cand_stage_load(g, t + 4, kv0, vv0);
+            cand_stage_load(g, t + 5, kv1, vv1);
+            __syncthreads();
+        }
+        store_block(a, X, r0, row, rvalid, m, l, o);
         if (X.lane == 0)
             *(lds_int *)X.scr = bad ? 1 : 0;
         __syncthreads(); // ends the pass: the ring is free, the verdicts are visible
@@ -754,7 +795,9 @@ hipError_t launch_stream(const Args &a, hipStream_t stream)
         const long long nblk_c = (long long)a.S * a.G / kBlockRows;
         cs.nblk_c = (int)nblk_c;
         cs.ngrp = (int)((nblk_c + kNW - 1) / kNW);
-        cs.bpp = (cs.nblk_c + cs.ngrp - 1) / cs.ngrp;
+        // Full passes first; the last one takes what is left.  With up to four blocks left every
+        // SIMD has at most one busy wavefront in it and the pass runs twice as fast.
+        cs.bpp = cs.nblk_c < kNW ? cs.nblk_c : kNW;
         const long long units = (long long)a.B * a.Hkv;
         const long long cpasses = (units + 7) / 8 * 8 * cs.ngrp;
         if (nblk_c * 10 >= (long long)cs.ngrp * kNW * 6 && cpasses <= 0x7fffffffLL - 8) {
