@@ -241,7 +241,7 @@ void bwd_dq_mfma_kernel(BwdArgs g, int npasses)
             if (work) // store_block divides by the sum of both half-waves' l: 1/(2 * 0.5/scale) = scale
                 store_block(ad, X, r0, row, rvalid, 0.f, 0.5f / a.scale, o);
             else
-                store_zero_block(ad, X, row);
+                store_zero_block(ad, X, r0, row);
         }
     }
 }

@@ -362,17 +362,24 @@ __device__ inline void store_block(const Args &a, const Ctx &X, int r0, const Ro
             rvalid ? (m + __builtin_log2f(ltot)) * kLn2 : -INFINITY;
 }
 
-// Zeros for a block that holds nothing but padding.
-__device__ inline void store_zero_block(const Args &a, const Ctx &X, const Row &row)
+// Zeros for the block of rows r0..r0+31 of the instruction, which holds nothing but padding; row
+// is this lane's own row of the block.  Stored like a computed block, 128 contiguous bytes of a
+// row per 8 lanes and instruction (whole cache lines, not sixteenths of them).
+__device__ inline void store_zero_block(const Args &a, const Ctx &X, int r0, const Row &row)
 {
-    if (!row.rin)
-        return;
-    unsigned short *orow = reinterpret_cast<unsigned short *>(a.out) + (long long)row.rb * a.o_sb +
-                           (long long)row.ri * a.o_ss + (long long)row.rh * a.o_sh;
 #pragma unroll
-    for (int u = 0; u < 8; ++u)
-        __builtin_nontemporal_store(uintx4{0, 0, 0, 0}, reinterpret_cast<uintx4 *>(orow + 64 * X.h + 8 * u));
-    if (a.lse && X.h == 0)
+    for (int u = 0; u < 4; ++u) {
+        const int r = r0 + 8 * u + (X.lane >> 3);
+        if (r < X.Mtot) {
+            const unsigned tok = fdiv((unsigned)r, a.div_g), gq = r - tok * a.G;
+            const unsigned bl = fdiv(tok, a.div_s), i = tok - bl * a.S;
+            unsigned short *dst = reinterpret_cast<unsigned short *>(a.out) + (long long)(X.cand0 + bl) * a.o_sb +
+                                  (long long)i * a.o_ss + (long long)(X.head * a.G + gq) * a.o_sh + 8 * (X.lane & 7);
+            __builtin_nontemporal_store(uintx4{0, 0, 0, 0}, reinterpret_cast<uintx4 *>(dst));
+            __builtin_nontemporal_store(uintx4{0, 0, 0, 0}, reinterpret_cast<uintx4 *>(dst + 64));
+        }
+    }
+    if (row.rin && a.lse && X.h == 0)
         a.lse[((long long)row.rb * a.Hq + row.rh) * a.S + row.ri] = -INFINITY;
 }
 
@@ -470,13 +477,17 @@ __device__ inline void store_block_rows(const Args &a, const Ctx &X, const Block
         a.lse[((long long)x.b * a.Hq + x.rh) * a.S + x.ri] = rvalid ? (m + __builtin_log2f(ltot)) * kLn2 : -INFINITY;
 }
 
-// Zeros for a block that holds nothing but padding.
+// Zeros for a block that holds nothing but padding (stored like a computed block: whole cache lines).
 __device__ inline void store_zero_block_rows(const Args &a, const Ctx &X, const BlockRows &x)
 {
-    unsigned char *orow = reinterpret_cast<unsigned char *>(a.out) + (long long)x.b * a.o_sb * 2 + x.o_off;
+    unsigned char *base = reinterpret_cast<unsigned char *>(a.out) + (long long)x.b * a.o_sb * 2;
 #pragma unroll
-    for (int u = 0; u < 8; ++u)
-        __builtin_nontemporal_store(uintx4{0, 0, 0, 0}, reinterpret_cast<uintx4 *>(orow + 128 * X.h + 16 * u));
+    for (int u = 0; u < 4; ++u) {
+        const unsigned off = (unsigned)__shfl((int)x.o_off, 8 * u + (X.lane >> 3), 64);
+        unsigned char *dst = base + (off + 16u * (X.lane & 7));
+        __builtin_nontemporal_store(uintx4{0, 0, 0, 0}, reinterpret_cast<uintx4 *>(dst));
+        __builtin_nontemporal_store(uintx4{0, 0, 0, 0}, reinterpret_cast<uintx4 *>(dst + 128));
+    }
     if (a.lse && X.h == 0)
         a.lse[((long long)x.b * a.Hq + x.rh) * a.S + x.ri] = -INFINITY;
 }

@@ -68,7 +68,7 @@ __device__ __attribute__((always_inline)) void general_block(const Args &a, cons
     const Row row = decode_row(a, X, blk);
     const bool rvalid = row.rin && (int)row.ri < clamp_len(a, row.rlen);
     if (__builtin_amdgcn_ballot_w64(rvalid) == 0) {
-        store_zero_block(a, X, row);
+        store_zero_block(a, X, r0, row);
         return;
     }
     uintx4 q[8];

@@ -125,7 +125,7 @@ __device__ __attribute__((always_inline)) void general_pass(const Args &a, Ctx &
             suffix_classic(a, X, r0, row, q, st);
             store_block(a, X, r0, row, rvalid, st.m, st.l, st.o);
         } else {
-            store_zero_block(a, X, row);
+            store_zero_block(a, X, r0, row);
         }
     }
 }
@@ -536,7 +536,7 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
             if (!nothing)
                 wg_short = true; // prefix too short for the pipeline: left to the general sweep below
             else if (ps.active)
-                store_zero_block(a, X, nxt);
+                store_zero_block(a, X, ps.blk * kBlockRows, nxt);
             p += gridDim.x;
             ps = make_cand_pass(a, cs, p, npasses, wave);
             nxt = decode_row(a, X, ps.blk, ps.head, ps.cand0);
@@ -602,7 +602,7 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
         // neighbour: same barriers, in the same order, as the path below.
         if (!active) {
             if (ps.active)
-                store_zero_block(a, X, row);
+                store_zero_block(a, X, r0, row);
             for (int t = 2; t + 1 <= T - 2; t += 2) {
                 stage_write(t + 2, kv0, vv0);
                 stage_write(t + 3, kv1, vv1);
