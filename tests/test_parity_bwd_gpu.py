@@ -147,3 +147,41 @@ def test_bwd_without_workspace_gives_the_same_bits(pk):
     for x, y, z in zip(with_ws, without, too_small):
         assert torch.equal(x.view(torch.int16), y.view(torch.int16))
         assert torch.equal(x.view(torch.int16), z.view(torch.int16))
+
+
+@pytest.mark.parametrize("impl", ["simple", "mfma"])
+@pytest.mark.parametrize("B,P,S,lo,hi", [
+    (6, 256, 24, 16, 24),       # resident-prefix dq kernel (32-bit row offsets within a candidate)
+    (3, 300, 33, 5, 33),        # streamed dq kernel, odd sizes
+])
+def test_bwd_strided_views_of_fused_buffers(pk, impl, B, P, S, lo, hi):
+    """q, k, v (and their gradients) as column slices of [B,S,(Hq+2Hkv)*D] buffers, out and dout
+    with a padded head stride: only strides change, the gradients must not."""
+    import torch
+    w = gen.custom_workload(f"bwd_strided_{P}_{S}", B, P, S, lo, hi, 8, 2, 128, "bf16", index=880)
+    inp = gen.make_inputs(w, pad="nan")
+    d = pu.to_device(inp)
+    Hq, Hkv, D = w.Hq, w.Hkv, w.D
+    nan = float("nan")
+    fused = torch.full((B, S, Hq + 2 * Hkv, D), nan, dtype=torch.bfloat16, device="cuda:0")
+    fused[:, :, :Hq] = d["q"]
+    fused[:, :, Hq:Hq + Hkv] = d["k_suf"]
+    fused[:, :, Hq + Hkv:] = d["v_suf"]
+    q, ks, vs = fused[:, :, :Hq], fused[:, :, Hq:Hq + Hkv], fused[:, :, Hq + Hkv:]
+    grads = torch.full_like(fused, nan)
+    dq, dk, dv = grads[:, :, :Hq], grads[:, :, Hq:Hq + Hkv], grads[:, :, Hq + Hkv:]
+    obuf = torch.full((B, S, Hq, 2 * D), nan, dtype=torch.bfloat16, device="cuda:0")
+    out = obuf[..., :D]
+    lse = torch.empty((B, Hq, S), dtype=torch.float32, device="cuda:0")
+    pk.pskv_attn_fwd(q, ks, vs, d["k_pre"], d["v_pre"], d["suf_len"], out=out, lse=lse, scale=inp.scale)
+    dout_host, dout64 = make_dout(inp, 881)
+    dbuf = torch.full_like(obuf, nan)
+    dbuf[..., :D] = torch.from_numpy(dout_host).view(torch.bfloat16).to("cuda:0")
+    dout = dbuf[..., :D]
+    pk.pskv_attn_bwd(q, ks, vs, d["k_pre"], d["v_pre"], d["suf_len"], out, lse, dout, dq=dq, dk_suf=dk, dv_suf=dv,
+                     impl=impl, scale=inp.scale)
+    torch.cuda.synchronize()
+    rq, rk, rv = pu.oracle_bwd(inp, dout64)
+    valid = np.arange(S)[None, :] < inp.suf_len[:, None]
+    for n, g, r in (("dq", dq, rq), ("dk_suf", dk, rk), ("dv_suf", dv, rv)):
+        compare_grad(pu.out_to_f64(g.contiguous()), r, valid, "bf16", f"strided {n}")

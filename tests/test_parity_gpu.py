@@ -93,11 +93,17 @@ def test_suf_len_null_means_full_length(pk, impl):
 
 
 @pytest.mark.parametrize("impl", ["simple", "mfma"])
-def test_strided_views_of_a_fused_qkv_buffer(pk, impl):
+@pytest.mark.parametrize("B,P,S,lo,hi", [
+    (5, 70, 18, 3, 18),         # general kernels
+    (6, 256, 24, 16, 24),       # resident prefix, pipelined kernel (32-bit row offsets within a candidate)
+    (3, 300, 32, 5, 32),        # streamed prefix, pipelined kernel
+    (2, 130, 160, 100, 160),    # passes cut out of one candidate
+])
+def test_strided_views_of_a_fused_qkv_buffer(pk, impl, B, P, S, lo, hi):
     """q, k, v as column slices of one [B,S,(Hq+2Hkv)*D] projection output, out with a
     padded head stride: only strides change, the result must not."""
     import torch
-    w = gen.custom_workload("strided", 5, 70, 18, 3, 18, 8, 2, 128, "bf16", index=401)
+    w = gen.custom_workload(f"strided_{P}_{S}", B, P, S, lo, hi, 8, 2, 128, "bf16", index=401)
     inp = gen.make_inputs(w, pad="nan")
     d = pu.to_device(inp)
     B, S, Hq, Hkv, D = w.B, w.S, w.Hq, w.Hkv, w.D
