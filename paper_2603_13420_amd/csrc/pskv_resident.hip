@@ -147,10 +147,18 @@ void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
     auto block_i_lo = [&](int blk) { return (int)fdiv(blk * kBlockRows, a.div_g) - block_cand(blk) * a.S; };
     // Advance to the next block of this wavefront that has a valid row; blocks of pure padding
     // on the way are stored as zeros here and now.
+    // A wavefront takes whole candidates - the nbc consecutive blocks of candidate w, then those of
+    // candidate w + (number of wavefronts on this virtual head), ... - so that a candidate's suffix
+    // K/V, which all of its blocks read, is fetched by one compute unit.
+    const int nbc = a.S * a.G / kBlockRows;
+    auto next_blk = [&](int blk) {
+        const int j = blk - block_cand(blk) * nbc;
+        return j + 1 < nbc ? blk + 1 : blk - j + blk_stride * nbc;
+    };
     auto skip_padding = [&](int blk) {
         while (blk < nblocks && block_i_lo(blk) >= len_uniform(a, X.cand0 + block_cand(blk))) {
             store_zero_block_rows(a, X, decode_block(a, X, blk, X.head, X.cand0));
-            blk += blk_stride;
+            blk = next_blk(blk);
         }
         return blk;
     };
@@ -160,7 +168,7 @@ void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
     const int T = (X.P + kTileKeys - 1) / kTileKeys;
 
     // first block of this wavefront: request its row decode and Q before the prefix copy
-    const int first_blk = (blockIdx.x / vh_slots) * kNW + __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int first_blk = ((blockIdx.x / vh_slots) * kNW + __builtin_amdgcn_readfirstlane(tid >> 6)) * nbc;
     bool any_bad = false;
     int blk = skip_padding(first_blk);
     BlockRows nxt = decode_block(a, X, blk < nblocks ? blk : nblocks - 1, X.head, X.cand0);
@@ -172,7 +180,7 @@ void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
     __syncthreads();
 
     if (T < 3) { // this instruction's prefix is too short for the pipeline: general path
-        for (int b2 = first_blk; b2 < nblocks; b2 += blk_stride)
+        for (int b2 = first_blk; b2 < nblocks; b2 = next_blk(b2))
             general_block(a, X, T, b2);
         continue;
     }
@@ -243,7 +251,7 @@ void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
         // Q has been used for the last time: the next block's row decode and Q take its place.
         // (Requested unconditionally, for a clamped block index past the end: a load under a
         // branch would have to be waited for and copied at the join.)
-        blk = skip_padding(blk + blk_stride);
+        blk = skip_padding(next_blk(blk));
         nxt = decode_block(a, X, blk < nblocks ? blk : nblocks - 1, X.head, X.cand0);
         load_q_block(a, X, nxt, q);
 
@@ -262,7 +270,7 @@ void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
     // Rare: some row met scores far above its first tile's maximum.  Whatever this wavefront
     // stored is replaced by the general path's result.
     if (any_bad)
-        for (int b2 = first_blk; b2 < nblocks; b2 += blk_stride)
+        for (int b2 = first_blk; b2 < nblocks; b2 = next_blk(b2))
             general_block(a, X, T, b2);
     } // virtual heads
 }
