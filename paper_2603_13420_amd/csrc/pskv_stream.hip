@@ -6,9 +6,9 @@
 // of one KV head are cut into groups of 256; a "pass" is one (KV head, group) pair.  A
 // persistent workgroup of 8 wavefronts takes passes in turn; each wavefront owns one 32-row
 // block of the group and all eight walk over the prefix together, tile by tile: the 512 threads
-// fetch the next 32-key tile of the single shared prefix K/V (Sec. 4.2: one copy for all
-// candidates) from L2 into registers while the current tiles are being used, write it into a
-// small ring of fragment-major LDS images, and meet at one barrier per tile.  Every tile is thus
+// request the coming 32-key tiles of the single shared prefix K/V (Sec. 4.2: one copy for all
+// candidates) from L2 straight into a small ring of fragment-major LDS images while the current
+// tiles are being used, and meet at one barrier per two tiles.  Every tile is thus
 // read once per 256 rows, whatever candidates those rows belong to, and the prefix itself is
 // read from HBM once: consecutive workgroup ids (one per XCD in turn) take passes of
 // consecutive heads, so the workgroups of one XCD keep returning to the same few heads and
@@ -152,13 +152,13 @@ void stream_general_kernel(Args a, int npasses)
 // ONE_STEP: S <= 32, the suffix is a single 32-key step.
 //
 // Ring protocol.  Step t of a pass (see pipe_tile) reads the K images of tiles t+1 and t+2 and
-// the V images of tiles t-1 and t.  Steps are taken two at a time.  At the top of the pair
-// (t, t+1) every thread writes its chunks of tiles t+2 and t+3 (fetched during the pair before)
-// into slots (t+2) % 8 and (t+3) % 8, requests tiles t+4 and t+5, and the workgroup meets at a
-// barrier; the pair then reads tiles t-1 .. t+3.  The slots written last held tiles t-6 and
-// t-5; a wavefront that has not reached this barrier yet is inside the pair before, which reads
-// nothing older than tile t-3.  Tile indices past the last tile are clamped to it: such a
-// write puts a copy of the last tile into a slot that no step reads any more.
+// the V images of tiles t-1 and t.  Steps are taken two at a time.  Tiles are requested with
+// direct-to-LDS loads, tile u into slot u % 8, tiles 0..6 at the start of the pass.  At the top
+// of the pair (t, t+1) every thread waits until its requests for the tiles up to t+3 have landed
+// (the vector memory counter retires requests in order: all but those of tile t+4 must be
+// complete), the workgroup meets at a barrier - after which everybody's parts of those tiles are
+// there and nobody reads tiles up to t-2 any more - and tiles t+5 and t+6 are requested into the
+// slots of tiles t-3 and t-2.  The pair then reads tiles t-1 .. t+3.
 // Rows past the end of a ragged last tile are fetched from the last prefix row instead: their
 // scores are masked and their weights are exactly zero, so finite data is all that is needed.
 // ------------------------------------------------------------------------------------------
@@ -170,15 +170,19 @@ struct Stager {
     int last;                           // index of the last tile
 };
 
-__device__ inline void stage_load(const Stager &g, int kt, uintx4 &kv, uintx4 &vv)
+// One 16-byte request per lane straight into LDS: lane l's bytes land at lds_base + 16*l (lds_base
+// is the same for the whole wavefront).  Written as an instruction rather than through the
+// compiler's builtin: the compiler would make every later LDS read wait for all such requests
+// still in flight.  Its own bookkeeping of the vector memory counter stays on the safe side:
+// requests it does not know of can only make its waits longer.  M0 carries the LDS address;
+// nothing else in this kernel uses M0.
+__device__ inline void request_to_lds(const unsigned char *g, lds_u8 *lds_base)
 {
-    const int ktc = kt < g.last ? kt : g.last;
-    const unsigned base = (unsigned)ktc * g.tile_stride;
-    const unsigned ko = base + (ktc == g.last ? g.k_off_last : g.k_off);
-    const unsigned vo = base + (ktc == g.last ? g.v_off_last : g.v_off);
-    kv = *reinterpret_cast<const uintx4 *>(g.kbase + ko);
-    vv = *reinterpret_cast<const uintx4 *>(g.vbase + vo);
+    const unsigned lds_addr = (unsigned)(unsigned long long)lds_base;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
 }
+// s_waitcnt immediate (gfx9 encoding): vector memory counter at most n (n < 16), the others untouched
+#define PSKV_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
 
 template <bool ONE_STEP>
 __global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
@@ -192,10 +196,12 @@ void stream_pipelined_kernel(Args a, int npasses)
     const int nblocks = (X.Mtot + kBlockRows - 1) / kBlockRows;
     auto kimg = [&](int t) { return X.k_lane + (t & (kRing - 1)) * kSlotBytes; };
     auto vimg = [&](int t) { return X.v_lane + (t & (kRing - 1)) * kSlotBytes; };
-    auto stage_write = [&](int kt, const uintx4 &kv, const uintx4 &vv) {
-        lds_u8 *slot = smem + (kt & (kRing - 1)) * kSlotBytes + tid * 16;
-        *(lds_u128 *)slot = kv;
-        *(lds_u128 *)(slot + kTileBytes) = vv;
+    // this thread's two requests for tile kt (kt <= the last tile), straight into slot kt % 8
+    auto request = [&](const Stager &g, int kt) {
+        const unsigned base = (unsigned)kt * g.tile_stride;
+        lds_u8 *slot = smem + (kt & (kRing - 1)) * kSlotBytes + wave * 1024;
+        request_to_lds(g.kbase + (base + (kt == g.last ? g.k_off_last : g.k_off)), slot);
+        request_to_lds(g.vbase + (base + (kt == g.last ? g.v_off_last : g.v_off)), slot + kTileBytes);
     };
 
     Stager g;
@@ -238,22 +244,30 @@ void stream_pipelined_kernel(Args a, int npasses)
         const bool rvalid = active && row.rin && (int)row.ri < clamp_len(a, row.rlen);
 
         // The ring is free here: the barrier that ended the previous pass was passed only by
-        // wavefronts that had finished reading it.  Tiles 0..3 go in at once.
-        uintx4 kv0, vv0, kv1, vv1;
-        {
-            uintx4 kv2, vv2, kv3, vv3;
-            stage_load(g, 0, kv0, vv0);
-            stage_load(g, 1, kv1, vv1);
-            stage_load(g, 2, kv2, vv2);
-            stage_load(g, 3, kv3, vv3);
-            stage_write(0, kv0, vv0);
-            stage_write(1, kv1, vv1);
-            stage_write(2, kv2, vv2);
-            stage_write(3, kv3, vv3);
-        }
-        stage_load(g, 4, kv0, vv0);
-        stage_load(g, 5, kv1, vv1);
+        // wavefronts that had finished reading it.  Tiles 0..6 are requested at once; the first
+        // steps need tiles 0..3.
+#pragma unroll
+        for (int u = 0; u < 7; ++u)
+            if (u < T)
+                request(g, u);
+        if (T >= 7)
+            PSKV_WAIT_VM(6);
+        else
+            PSKV_WAIT_VM(0);
         __syncthreads();
+        // Top of the pair (t, t+1): tiles up to t+3 have landed for everyone (tile t+4 may still be
+        // in flight); nobody reads tiles up to t-2 any more: their slots take tiles t+5 and t+6.
+        auto pair_top = [&](int t) {
+            if (t + 4 <= T - 1)
+                PSKV_WAIT_VM(2);
+            else
+                PSKV_WAIT_VM(0);
+            __syncthreads();
+            if (t + 5 <= T - 1)
+                request(g, t + 5);
+            if (t + 6 <= T - 1)
+                request(g, t + 6);
+        };
 
         // the block's suffix: candidate sb, keys 0..skmax
         const int sb = (int)fdiv(fdiv(r0, a.div_g), a.div_s);
@@ -300,21 +314,15 @@ void stream_pipelined_kernel(Args a, int npasses)
                                                                pre, q, sB, sA, X.c, m, 0, l, pA, pB, o);               \
     } while (0)
         int t = 2;
-        for (; t + 3 <= T - 2; t += 2) { // tiles t+2, t+3 into the ring, tiles t+4, t+5 requested, barrier
-            stage_write(t + 2, kv0, vv0);
-            stage_write(t + 3, kv1, vv1);
-            stage_load(g, t + 4, kv0, vv0);
-            stage_load(g, t + 5, kv1, vv1);
-            __syncthreads();
+        for (; t + 3 <= T - 2; t += 2) {
+            pair_top(t);
             PSKV_STEP_PAIR(t);
         }
         // The last pair requests no further tiles; the suffix K fragments, needed two or three
         // steps from here, are requested once the staging registers are free.
         if (t + 1 <= T - 2) {
-            stage_write(t + 2, kv0, vv0);
-            stage_write(t + 3, kv1, vv1);
+            pair_top(t);
             load_suffix_k(a, X, X.cand0 + sb, 0, skmax, skf);
-            __syncthreads();
             PSKV_STEP_PAIR(t);
             t += 2;
         } else {
