@@ -220,7 +220,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (the path needs no exchange between "
-              "candidates or KV heads; sharding is described in DESIGN.md). Use --gpus 1.",
+              "candidates or KV heads, so it would shard by candidates or by KV heads). Use --gpus 1.",
               file=sys.stderr)
         sys.exit(2)
 
