@@ -93,7 +93,7 @@ __device__ __attribute__((always_inline)) void general_block(const Args &a, cons
 // pair; there are VH = Np*Hkv of them, each with its own prefix and its own C*S*G stacked
 // rows.  The grid is per_vh * vh_slots workgroups: workgroup w serves virtual heads
 // w % vh_slots, + vh_slots, ... (consecutive workgroup ids, one per XCD in turn, take
-// consecutive KV heads) and, within each, the row blocks of slice w / vh_slots out of per_vh.
+// consecutive KV heads) and, within each, a share w / vh_slots out of per_vh of the row blocks.
 __global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
 void resident_general_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
 {
@@ -135,7 +135,6 @@ void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
     const int tid = threadIdx.x;
     Ctx X = make_ctx(a, smem, max_tiles, tid);
     const int nblocks = (X.Mtot + kBlockRows - 1) / kBlockRows;
-    const int blk_stride = per_vh * kNW;
     const int VH = a.Np * a.Hkv;
     auto kimg = [&](int t) { return X.k_lane + t * kTileBytes; };
     auto vimg = [&](int t) { return X.v_lane + t * kTileBytes; };
@@ -147,18 +146,24 @@ void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
     auto block_i_lo = [&](int blk) { return (int)fdiv(blk * kBlockRows, a.div_g) - block_cand(blk) * a.S; };
     // Advance to the next block of this wavefront that has a valid row; blocks of pure padding
     // on the way are stored as zeros here and now.
-    // A wavefront takes whole candidates - the nbc consecutive blocks of candidate w, then those of
-    // candidate w + (number of wavefronts on this virtual head), ... - so that a candidate's suffix
-    // K/V, which all of its blocks read, is fetched by one compute unit.
-    const int nbc = a.S * a.G / kBlockRows;
-    auto next_blk = [&](int blk) {
-        const int j = blk - block_cand(blk) * nbc;
-        return j + 1 < nbc ? blk + 1 : blk - j + blk_stride * nbc;
-    };
+    // Every wavefront takes one contiguous range of blocks, so that a candidate's suffix K/V, which
+    // all of its blocks read, is fetched by one compute unit.  The workgroup's share of the virtual
+    // head's blocks is cut into four parts, one per SIMD.  The two wavefronts of a SIMD (slots w and
+    // w + 4) are not served alike: the one launched first wins the arbitration for the matrix cores
+    // and gets through a block about a fifth faster, so it takes 7/12 of the SIMD's part and the
+    // other one the rest; with equal shares the second one runs on alone for the last sixth of the
+    // launch (measured: 14:10 beats 12:12 by 2-3 %, 13:11 and 15:9 lie between).
+    const int wslot = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int slice = blockIdx.x / vh_slots;
+    const int wg_lo = (int)((long long)nblocks * slice / per_vh), wg_hi = (int)((long long)nblocks * (slice + 1) / per_vh);
+    const int simd = wslot & 3;
+    const int part_lo = wg_lo + (wg_hi - wg_lo) * simd / 4, part_hi = wg_lo + (wg_hi - wg_lo) * (simd + 1) / 4;
+    const int split = part_lo + ((part_hi - part_lo) * 7 + 6) / 12;
+    const int blk_lo = wslot < 4 ? part_lo : split, blk_hi = wslot < 4 ? split : part_hi;
     auto skip_padding = [&](int blk) {
-        while (blk < nblocks && block_i_lo(blk) >= len_uniform(a, X.cand0 + block_cand(blk))) {
+        while (blk < blk_hi && block_i_lo(blk) >= len_uniform(a, X.cand0 + block_cand(blk))) {
             store_zero_block_rows(a, X, decode_block(a, X, blk, X.head, X.cand0));
-            blk = next_blk(blk);
+            ++blk;
         }
         return blk;
     };
@@ -168,10 +173,10 @@ void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
     const int T = (X.P + kTileKeys - 1) / kTileKeys;
 
     // first block of this wavefront: request its row decode and Q before the prefix copy
-    const int first_blk = ((blockIdx.x / vh_slots) * kNW + __builtin_amdgcn_readfirstlane(tid >> 6)) * nbc;
+    const int first_blk = blk_lo;
     bool any_bad = false;
     int blk = skip_padding(first_blk);
-    BlockRows nxt = decode_block(a, X, blk < nblocks ? blk : nblocks - 1, X.head, X.cand0);
+    BlockRows nxt = decode_block(a, X, blk < blk_hi ? blk : nblocks - 1, X.head, X.cand0);
     uintx4 q[8]; // this block's Q fragments until their last use, then the next block's
     load_q_block(a, X, nxt, q);
 
@@ -180,12 +185,12 @@ void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
     __syncthreads();
 
     if (T < 3) { // this instruction's prefix is too short for the pipeline: general path
-        for (int b2 = first_blk; b2 < nblocks; b2 = next_blk(b2))
+        for (int b2 = first_blk; b2 < blk_hi; ++b2)
             general_block(a, X, T, b2);
         continue;
     }
 
-    while (blk < nblocks) {
+    while (blk < blk_hi) {
         const BlockRows row = nxt;
         // the block's suffix step: keys 0..skmax of its candidate
         const int i_hi = (int)fdiv(blk * kBlockRows + kBlockRows - 1, a.div_g) - (row.b - X.cand0) * a.S;
@@ -251,8 +256,8 @@ void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
         // Q has been used for the last time: the next block's row decode and Q take its place.
         // (Requested unconditionally, for a clamped block index past the end: a load under a
         // branch would have to be waited for and copied at the join.)
-        blk = skip_padding(next_blk(blk));
-        nxt = decode_block(a, X, blk < nblocks ? blk : nblocks - 1, X.head, X.cand0);
+        blk = skip_padding(blk + 1);
+        nxt = decode_block(a, X, blk < blk_hi ? blk : nblocks - 1, X.head, X.cand0);
         load_q_block(a, X, nxt, q);
 
         // ---- suffix step: causal mask and weights under the value product of the last prefix
@@ -270,7 +275,7 @@ void resident_pipelined_kernel(Args a, int per_vh, int vh_slots, int max_tiles)
     // Rare: some row met scores far above its first tile's maximum.  Whatever this wavefront
     // stored is replaced by the general path's result.
     if (any_bad)
-        for (int b2 = first_blk; b2 < nblocks; b2 = next_blk(b2))
+        for (int b2 = first_blk; b2 < blk_hi; ++b2)
             general_block(a, X, T, b2);
     } // virtual heads
 }
