@@ -49,12 +49,12 @@ def alg_counts(w, suf_len, pre_len=None):
 # the factor by which the same counter under- or over-reads a plain copy kernel of known size.
 # Offline measurements: the commands and raw readings are in profiles/*_hbm_traffic.txt.
 HBM_TRAFFIC = {
-    "gqa8b_bf16": {"fetch_kib": 140615.0, "fetch_scale": 2.0, "write_kib": 203777.0, "write_scale": 1.0},
+    "gqa8b_bf16": {"fetch_kib": 145367.0, "fetch_scale": 2.0, "write_kib": 203270.0, "write_scale": 1.0},
     "ldec_gqa8b_bf16": {"fetch_kib": 237993.6, "fetch_scale": 2.0, "write_kib": 327680.1, "write_scale": 1.0},
     "longprefix_bf16": {"fetch_kib": 63003.5, "fetch_scale": 2.0, "write_kib": 66566.3, "write_scale": 1.0},
-    "multi8_gqa8b_bf16": {"fetch_kib": 144438.5, "fetch_scale": 2.0, "write_kib": 203776.0, "write_scale": 1.0},
+    "multi8_gqa8b_bf16": {"fetch_kib": 145372.0, "fetch_scale": 2.0, "write_kib": 203264.0, "write_scale": 1.0},
     "mha13b_bf16": {"fetch_kib": 3919561.6, "fetch_scale": 2.0, "write_kib": 2622464.0, "write_scale": 1.0},
-    "multi32_gqa8b_bf16": {"fetch_kib": 150726.0, "fetch_scale": 2.0, "write_kib": 203776.0, "write_scale": 1.0},
+    "multi32_gqa8b_bf16": {"fetch_kib": 154823.0, "fetch_scale": 2.0, "write_kib": 203264.0, "write_scale": 1.0},
     "multi4_long_bf16": {"fetch_kib": 60091.5, "fetch_scale": 2.0, "write_kib": 66560.0, "write_scale": 1.0},
     "ldec_qwen7b_bf16": {"fetch_kib": 180835.4, "fetch_scale": 2.0, "write_kib": 286720.0, "write_scale": 1.0},
     "mha7b_bf16": {"fetch_kib": 127696.5, "fetch_scale": 2.0, "write_kib": 81920.6, "write_scale": 1.0},
