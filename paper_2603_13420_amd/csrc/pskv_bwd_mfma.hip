@@ -106,6 +106,8 @@ void bwd_dq_mfma_kernel(BwdArgs g, int npasses)
         const bool rvalid = active && row.rin && (int)row.ri < clamp_len(a, row.rlen);
         const bool work = __builtin_amdgcn_ballot_w64(rvalid) != 0;
 
+        // requested first, so that it is there with the rows below and costs no round trip of its own
+        const float lse2 = (row.rin ? a.lse[((long long)row.rb * a.Hq + row.rh) * a.S + row.ri] : 0.f) * kLog2e;
         uintx4 q[8], dof[8];
         load_q(a, X, row, q);
         load_o_like(a, X, row, g.dout, dof);
@@ -124,7 +126,6 @@ void bwd_dq_mfma_kernel(BwdArgs g, int npasses)
         }
         if (g.delta && active && row.rin && X.h == 0)
             g.delta[((long long)row.rb * a.Hq + row.rh) * a.S + row.ri] = drow;
-        const float lse2 = (row.rin ? a.lse[((long long)row.rb * a.Hq + row.rh) * a.S + row.ri] : 0.f) * kLog2e;
 
         floatx16 o[4];
 #pragma unroll
@@ -341,6 +342,8 @@ void bwd_dq_resident_kernel(BwdArgs g, int per_vh, int vh_slots, int max_tiles)
             const int i_hi = (int)fdiv(blk * kBlockRows + kBlockRows - 1, a.div_g) - (row.b - X.cand0) * a.S;
             const int kmax = i_hi < row.len - 1 ? i_hi : row.len - 1;
 
+            // requested first, so that it is there with the rows below and costs no round trip of its own
+            const float lse2 = a.lse[((long long)row.b * a.Hq + row.rh) * a.S + row.ri] * kLog2e;
             uintx4 q[8], dof[8];
             load_q_block(a, X, row, q);
             float drow = 0.f; // <dout_row, out_row>: this lane's 64 columns, then the other half-wave's
@@ -365,7 +368,6 @@ void bwd_dq_resident_kernel(BwdArgs g, int per_vh, int vh_slots, int max_tiles)
             }
             if (g.delta && X.h == 0)
                 g.delta[((long long)row.b * a.Hq + row.rh) * a.S + row.ri] = drow;
-            const float lse2 = a.lse[((long long)row.b * a.Hq + row.rh) * a.S + row.ri] * kLog2e;
 
             floatx16 o[4];
 #pragma unroll
@@ -612,6 +614,7 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
             // everything the block needs from global memory is requested here, in one round trip
             uintx4 qh[4], doh[4]; // this half's columns of q and dout, kept for the second products
             float drow = 0.f;
+            const float lse_row = a.lse[((long long)b * a.Hq + k * a.G + gq) * a.S + ri] * kLog2e;
             {
                 uintx4 qf[8], dof[8], of[HAS_DELTA ? 1 : 8];
 #pragma unroll
@@ -647,7 +650,7 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
             }
             // row quantities to LDS, then each lane fetches those of the 16 rows its elements belong to
             if (X.h == 0) {
-                aux_lse[X.c32] = a.lse[((long long)b * a.Hq + k * a.G + gq) * a.S + ri] * kLog2e;
+                aux_lse[X.c32] = lse_row;
                 aux_drow[X.c32] = drow;
                 aux_i[X.c32] = rvalid ? (float)ri : -1.f;
             }
