@@ -41,6 +41,16 @@ __device__ inline void load_o_like(const Args &a, const Ctx &X, const Row &x, co
         dst[ks] = ld_global16(r + 16 * ks);
 }
 
+// Where <dout_row, out_row> of query row (candidate b, query head rh, suffix position ri) sits in
+// the workspace: in the order of the stacked rows of its KV head, ((b*Hkv + k)*S + ri)*G + g, so
+// that the 32 rows of a block are 128 contiguous bytes for the kernel that writes them and for
+// the one that reads them back.
+__device__ inline long long delta_index(const Args &a, long long b, int rh, int ri)
+{
+    const int k = (int)fdiv((unsigned)rh, a.div_g), gq = rh - k * a.G;
+    return ((b * a.Hkv + k) * a.S + ri) * a.G + gq;
+}
+
 __device__ inline float bf16_lo(unsigned w) { return __uint_as_float(w << 16); }
 __device__ inline float bf16_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
 
@@ -108,13 +118,20 @@ void bwd_dq_mfma_kernel(BwdArgs g, int npasses)
 
         // requested first, so that it is there with the rows below and costs no round trip of its own
         const float lse2 = (row.rin ? a.lse[((long long)row.rb * a.Hq + row.rh) * a.S + row.ri] : 0.f) * kLog2e;
+        // Rows past their candidate's length take the data of its last position (never fetched
+        // otherwise): what they compute is finite and stored as zero.
+        Row rld = row;
+        {
+            const int len = clamp_len(a, row.rlen);
+            rld.ri = (int)row.ri < len ? row.ri : (len > 0 ? (unsigned)(len - 1) : 0u);
+        }
         uintx4 q[8], dof[8];
-        load_q(a, X, row, q);
-        load_o_like(a, X, row, g.dout, dof);
+        load_q(a, X, rld, q);
+        load_o_like(a, X, rld, g.dout, dof);
         float drow = 0.f; // <dout_row, out_row>: this lane's 64 columns, then the other half-wave's
         {
             uintx4 of[8];
-            load_o_like(a, X, row, a.out, of);
+            load_o_like(a, X, rld, a.out, of);
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
@@ -124,8 +141,8 @@ void bwd_dq_mfma_kernel(BwdArgs g, int npasses)
                 }
             drow += __shfl_xor(drow, 32, 64);
         }
-        if (g.delta && active && row.rin && X.h == 0)
-            g.delta[((long long)row.rb * a.Hq + row.rh) * a.S + row.ri] = drow;
+        if (g.delta && rvalid && X.h == 0) // kept in the order of the stacked rows: see delta_index
+            g.delta[delta_index(a, row.rb, row.rh, row.ri)] = drow;
 
         floatx16 o[4];
 #pragma unroll
@@ -296,7 +313,6 @@ void bwd_dq_resident_kernel(BwdArgs g, int per_vh, int vh_slots, int max_tiles)
     const int nblocks = (X.Mtot + kBlockRows - 1) / kBlockRows;
     const int blk_stride = per_vh * kNW;
     const int VH = a.Np * a.Hkv;
-    const TileSlot t = make_tile_slot(tid);
     // the gradient goes out through the forward pass's store routine: dq is laid out like q
     Args ad = a;
     ad.out = g.dq;
@@ -307,25 +323,34 @@ void bwd_dq_resident_kernel(BwdArgs g, int per_vh, int vh_slots, int max_tiles)
         set_vhead(a, X, vh);
         const int T = (X.P + kTileKeys - 1) / kTileKeys;
         __syncthreads(); // every wavefront is done with the images of the virtual head before
-        {
-            uintx4 vk[kDqMaxTiles], kk[kDqMaxTiles];
+        { // four tiles at a time: more would not fit the register file next to what the block loop keeps
+            // The thread's place in the images is worked out here, from a thread id the compiler
+            // cannot trace back: kept across the block loop instead, these values would be spilled.
+            int tid_here = tid;
+            asm volatile("" : "+v"(tid_here));
+            const TileSlot t = make_tile_slot(tid_here);
             const int last = X.P > 0 ? X.P - 1 : 0;
-#pragma unroll
-            for (int kt = 0; kt < kDqMaxTiles; ++kt)
-                if (kt < T) {
-                    const int kkey = kt * kTileKeys + t.k_row, vkey = kt * kTileKeys + t.v_row;
-                    vk[kt] = ld_global16(X.vpg + (long long)(kkey < X.P ? kkey : last) * a.kp_sp + t.k_chunk * 8);
-                    kk[kt] = ld_global16(X.kpg + (long long)(vkey < X.P ? vkey : last) * a.kp_sp + t.v_chunk * 8);
-                }
-            const int fr = tid >> 5, p5 = tid & 31;
+            const int fr = tid_here >> 5, p5 = tid_here & 31;
             const int pos = p5 ^ (p5 >> 4) ^ (8 * (fr & 1));
 #pragma unroll
-            for (int kt = 0; kt < kDqMaxTiles; ++kt)
-                if (kt < T) {
-                    const int kkey = kt * kTileKeys + t.k_row, vkey = kt * kTileKeys + t.v_row;
-                    *(lds_u128 *)(vrm + kt * kTileBytes + tid * 16) = kkey < X.P ? vk[kt] : uintx4{0, 0, 0, 0};
-                    *(lds_u128 *)(ktr + kt * kTileBytes + fr * 512 + pos * 16) = vkey < X.P ? kk[kt] : uintx4{0, 0, 0, 0};
-                }
+            for (int kt0 = 0; kt0 < kDqMaxTiles; kt0 += 4) {
+                uintx4 vk[4] = {}, kk[4] = {}; // defined on every path: nothing of them outlives the iteration
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (kt0 + i < T) {
+                        const int kkey = (kt0 + i) * kTileKeys + t.k_row, vkey = (kt0 + i) * kTileKeys + t.v_row;
+                        vk[i] = ld_global16(X.vpg + (long long)(kkey < X.P ? kkey : last) * a.kp_sp + t.k_chunk * 8);
+                        kk[i] = ld_global16(X.kpg + (long long)(vkey < X.P ? vkey : last) * a.kp_sp + t.v_chunk * 8);
+                    }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (kt0 + i < T) {
+                        const int kt = kt0 + i;
+                        const int kkey = kt * kTileKeys + t.k_row, vkey = kt * kTileKeys + t.v_row;
+                        *(lds_u128 *)(vrm + kt * kTileBytes + tid_here * 16) = kkey < X.P ? vk[i] : uintx4{0, 0, 0, 0};
+                        *(lds_u128 *)(ktr + kt * kTileBytes + fr * 512 + pos * 16) = vkey < X.P ? kk[i] : uintx4{0, 0, 0, 0};
+                    }
+            }
         }
         __syncthreads();
 
@@ -348,9 +373,12 @@ void bwd_dq_resident_kernel(BwdArgs g, int per_vh, int vh_slots, int max_tiles)
             load_q_block(a, X, row, q);
             float drow = 0.f; // <dout_row, out_row>: this lane's 64 columns, then the other half-wave's
             {
+                // rows past the candidate's length take dout and out of its last position, as they do for q
+                const int rld = row.ri < row.len ? row.ri : row.len - 1;
+                const unsigned ld_off = ((unsigned)rld * (unsigned)a.o_ss + (unsigned)row.rh * (unsigned)a.o_sh) * 2u;
                 const long long obase = (long long)row.b * a.o_sb * 2;
-                const unsigned char *dorow = reinterpret_cast<const unsigned char *>(g.dout) + obase + (row.o_off + 16u * X.h);
-                const unsigned char *orow = reinterpret_cast<const unsigned char *>(a.out) + obase + (row.o_off + 16u * X.h);
+                const unsigned char *dorow = reinterpret_cast<const unsigned char *>(g.dout) + obase + (ld_off + 16u * X.h);
+                const unsigned char *orow = reinterpret_cast<const unsigned char *>(a.out) + obase + (ld_off + 16u * X.h);
                 uintx4 of[8];
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks) {
@@ -366,8 +394,8 @@ void bwd_dq_resident_kernel(BwdArgs g, int per_vh, int vh_slots, int max_tiles)
                     }
                 drow += __shfl_xor(drow, 32, 64);
             }
-            if (g.delta && X.h == 0)
-                g.delta[((long long)row.b * a.Hq + row.rh) * a.S + row.ri] = drow;
+            if (g.delta && row.ri < row.len && X.h == 0) // one 128-byte line per block: see delta_index
+                g.delta[delta_index(a, row.b, row.rh, row.ri)] = drow;
 
             floatx16 o[4];
 #pragma unroll
@@ -625,7 +653,7 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
                         of[ks] = ld_global16(outb + ooff + 16 * ks);
                 }
                 if constexpr (HAS_DELTA) // left there by the dq kernel (the clamped row is a valid one, hence written)
-                    drow = g.delta[((long long)b * a.Hq + k * a.G + gq) * a.S + ri];
+                    drow = g.delta[delta_index(a, b, k * a.G + gq, ri)];
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks)
                     s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qf[ks]), as_bf16x8(kf[ks]), s, 0, 0, 0);
