@@ -29,8 +29,12 @@ constexpr int kMaxTiles = 8; // resident prefix: at most 256 keys
 // latencies overlap.
 __device__ inline void stage_prefix(const Args &a, const Ctx &X, int ntiles, lds_u8 *kimg, lds_u8 *vimg, int tid)
 {
+    // The thread's place in the images is worked out here, from a thread id the compiler cannot
+    // trace back, and the staging registers are defined on every path: kept alive across the
+    // block loops of the callers instead, these values would be spilled.
+    asm volatile("" : "+v"(tid));
     const TileSlot t = make_tile_slot(tid);
-    uintx4 kv[kMaxTiles], vv[kMaxTiles];
+    uintx4 kv[kMaxTiles] = {}, vv[kMaxTiles] = {};
 #pragma unroll
     for (int kt = 0; kt < kMaxTiles; ++kt)
         if (kt < ntiles)
