@@ -49,15 +49,15 @@ def alg_counts(w, suf_len, pre_len=None):
 # the factor by which the same counter under- or over-reads a plain copy kernel of known size.
 # Offline measurements: the commands and raw readings are in profiles/*_hbm_traffic.txt.
 HBM_TRAFFIC = {
-    "gqa8b_bf16": {"fetch_kib": 145367.0, "fetch_scale": 2.0, "write_kib": 203270.0, "write_scale": 1.0},
+    "gqa8b_bf16": {"fetch_kib": 143007.0, "fetch_scale": 2.0, "write_kib": 197636.0, "write_scale": 1.0},
     "ldec_gqa8b_bf16": {"fetch_kib": 237993.6, "fetch_scale": 2.0, "write_kib": 327680.1, "write_scale": 1.0},
     "longprefix_bf16": {"fetch_kib": 63003.5, "fetch_scale": 2.0, "write_kib": 66566.3, "write_scale": 1.0},
-    "multi8_gqa8b_bf16": {"fetch_kib": 145372.0, "fetch_scale": 2.0, "write_kib": 203264.0, "write_scale": 1.0},
+    "multi8_gqa8b_bf16": {"fetch_kib": 142711.0, "fetch_scale": 2.0, "write_kib": 197632.0, "write_scale": 1.0},
     "mha13b_bf16": {"fetch_kib": 3919561.6, "fetch_scale": 2.0, "write_kib": 2622464.0, "write_scale": 1.0},
-    "multi32_gqa8b_bf16": {"fetch_kib": 154823.0, "fetch_scale": 2.0, "write_kib": 203264.0, "write_scale": 1.0},
+    "multi32_gqa8b_bf16": {"fetch_kib": 151957.0, "fetch_scale": 2.0, "write_kib": 197632.0, "write_scale": 1.0},
     "multi4_long_bf16": {"fetch_kib": 60091.5, "fetch_scale": 2.0, "write_kib": 66560.0, "write_scale": 1.0},
     "ldec_qwen7b_bf16": {"fetch_kib": 180835.4, "fetch_scale": 2.0, "write_kib": 286720.0, "write_scale": 1.0},
-    "mha7b_bf16": {"fetch_kib": 127696.5, "fetch_scale": 2.0, "write_kib": 81920.6, "write_scale": 1.0},
+    "mha7b_bf16": {"fetch_kib": 129055.0, "fetch_scale": 2.0, "write_kib": 81921.7, "write_scale": 1.0},
 }
 
 
@@ -101,6 +101,12 @@ def cpu_baseline_multi(inp, budget_s=12.0):
     return {"value": done / t_total, "unit": "candidates/s", "cores": orc.threads(), "kind": "oracle",
             "sample": f"{n} instructions with their {w.C} candidates each (those of {w.name} in order, wrapping "
                       f"round; all heads), {t_total:.1f} s of oracle time"}
+
+
+# The same for one backward call (its two kernels together).
+HBM_TRAFFIC_BWD = {
+    "gqa8b_bf16": {"fetch_kib": 302485.0 + 208528.0, "fetch_scale": 2.0, "write_kib": 199247.7 + 98304.0, "write_scale": 1.0},
+}
 
 
 def bench_backward(args):
@@ -169,7 +175,9 @@ def bench_backward(args):
            "alg_bytes_per_step": bytes_}
     hbm["frac"] = hbm["achieved"] / hbm["peak"]
     roof, other = (hbm, compute) if bytes_ / (PEAK_HBM_GBS * 1e9) >= flops / (compute["peak"] * 1e12) else (compute, hbm)
-    roof["traffic"] = None
+    tr = HBM_TRAFFIC_BWD.get(w.name) if args.impl == "auto" else None
+    roof["traffic"] = (tr["fetch_kib"] * tr["fetch_scale"] + tr["write_kib"] * tr["write_scale"]) * 1024 if tr else None
+    roof["traffic_unit"] = "bytes per step"
     roof["kernel_ms"] = kern_ms
     line = {"metric": "candidate suffixes/sec per attention layer, backward pass", "value": w.B / (ms_per_step * 1e-3),
             "unit": "candidates/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms_per_step,
