@@ -64,6 +64,8 @@ def test_bwd_tiny_f32(pk):
     (3, 0, 24, 0, 24, 4, 1),        # no prefix; one candidate may be empty
     (3, 300, 33, 5, 33, 14, 2),     # group 7, odd sizes, long prefix
     (2, 700, 70, 33, 70, 2, 2),     # long suffix-side segment
+    (3, 128, 160, 100, 160, 8, 2),  # the scoring workload in small: resident prefix, five suffix steps
+    (2, 100, 96, 40, 96, 14, 2),    # the same with a query-head group of 7 and a ragged prefix tile
 ])
 def test_bwd_small_shapes_bf16(pk, impl, B, P, S, lo, hi, Hq, Hkv):
     w = gen.custom_workload(f"bwd_{B}_{P}_{S}_{Hq}_{Hkv}", B, P, S, lo, hi, Hq, Hkv, 128, "bf16", index=800 + B + P)
