@@ -29,6 +29,13 @@ BF16_REL = 2.0 ** -7
 # row that sees only a handful of keys (|out_row| is then not averaged down) this alone is about
 # 1e-2 of the gradient's standard deviation at the worst element of 1e5, so the std term is 3e-2.
 BF16_TIGHT_STD_GRAD = 3e-2
+# Rows that see fewer than FEW_KEYS keys (no or hardly any prefix, first suffix positions): their
+# out_row is the average of a few V rows, as large as a V row itself, the rounding of `out` weighs
+# in fully, and an independent fp32 vector-ALU implementation handed the same rounded `out`
+# deviates from the exact gradient by the same 3.3e-2 std at the worst such element as the
+# matrix-core kernels.  For the query gradient of those rows the std term is 1e-1.
+BF16_TIGHT_STD_GRAD_FEW = 1e-1
+FEW_KEYS = 8
 
 
 def to_device(inp: gen.Inputs, device="cuda:0"):
@@ -128,8 +135,9 @@ def make_dout(inp, seed):
     return a, a.astype(np.float64)
 
 
-def compare_grad(got, ref, valid_rows, dtype, what):
-    """Same bars as the forward pass, applied to a gradient tensor [B,S,H,D]."""
+def compare_grad(got, ref, valid_rows, dtype, what, few_keys_rows=None):
+    """Same bars as the forward pass, applied to a gradient tensor [B,S,H,D].  few_keys_rows:
+    [B,S] mask of the rows that take the wider std term (see BF16_TIGHT_STD_GRAD_FEW)."""
     assert not np.isnan(got).any(), f"{what}: NaN"
     assert np.all(got[~valid_rows] == 0.0), f"{what}: padded rows must be exactly 0"
     g, r = got[valid_rows], ref[valid_rows]
@@ -148,7 +156,10 @@ def compare_grad(got, ref, valid_rows, dtype, what):
         assert res["max_rel"] <= F32_REL, f"{what}: relative error {res['max_rel']:.3e}"
     else:
         sd = float(r.std())
-        bound = BF16_REL * np.abs(r) + BF16_TIGHT_STD_GRAD * sd
+        std_term = np.full(valid_rows.shape, BF16_TIGHT_STD_GRAD)
+        if few_keys_rows is not None:
+            std_term[few_keys_rows] = BF16_TIGHT_STD_GRAD_FEW
+        bound = BF16_REL * np.abs(r) + (std_term[valid_rows] * sd)[:, None, None]
         res["std_ref"] = sd
         res["tight_ratio"] = float((err / np.maximum(bound, 1e-300)).max())
         # the absolute bar of the forward pass, for tensors whose elements are sums of many terms of
