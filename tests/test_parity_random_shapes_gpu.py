@@ -62,3 +62,34 @@ def test_random_shape(pk, case):
     for name, got, r in (("dq", dq, rq), ("dk_suf", dk, rk), ("dv_suf", dv, rv)):
         pu.compare_grad(pu.out_to_f64(got), r, valid, "bf16", f"{w.name} {name}",
                         few_keys_rows=few if name == "dq" else None)
+
+
+def draw_multi_shape(case: int):
+    rng = np.random.default_rng(1977 + case)
+    G = int(rng.choice([1, 2, 4, 7]))
+    Hkv = int(rng.choice([1, 2, 4]))
+    P = int(rng.choice([rng.integers(1, 96), rng.integers(96, 257), rng.integers(257, 600)]))
+    plo = int(rng.integers(0, P + 1))
+    S = int(rng.choice([rng.integers(1, 33), rng.integers(33, 80), 8 * rng.integers(1, 11)]))
+    return int(rng.integers(1, 6)), int(rng.integers(1, 5)), P, plo, P, S, int(rng.integers(0, S + 1)), S, G * Hkv, Hkv
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_random_multi_shape(pk, case):
+    """The multi-instruction form on random shapes: prefixes of random real lengths (left-padded,
+    padding NaN), forward through whatever kernel the library picks."""
+    import torch
+    Np, C, P, plo, phi, S, lo, hi, Hq, Hkv = draw_multi_shape(case)
+    w = gen.custom_multi_workload(f"mrand{case}", Np, C, P, plo, phi, S, lo, hi, Hq, Hkv, 128, "bf16", index=1300 + case)
+    inp = gen.make_multi_inputs(w, pad="nan")
+    d = pu.to_device_multi(inp)
+    print(f"[case] random multi shape {case}: Np={Np} C={C} P={P} pre_len={inp.pre_len.tolist()} S={S} len={lo}..{hi} "
+          f"Hq={Hq} Hkv={Hkv} seed={w.seed}", flush=True)
+    lse = torch.full((w.B, Hq, S), 123.0, device="cuda:0")
+    out = torch.full_like(d["q"], float("nan"))
+    pk.pskv_attn_fwd_multi(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["pre_len"], d["suf_len"],
+                           out=out, lse=lse, scale=inp.scale)
+    torch.cuda.synchronize()
+    ref, ref_lse = pu.oracle_out_multi(inp, want_lse=True)
+    pu.compare_lse(lse.cpu().numpy().astype(np.float64), ref_lse, inp.suf_len, "bf16", w.name)
+    pu.compare(pu.out_to_f64(out), ref, inp.suf_len, "bf16", w.name)
