@@ -90,3 +90,46 @@ def test_tensors_beyond_2_31_elements(pk, B, P, S, lo, hi, Hq, Hkv, backward):
     for name, got, r in (("dq", dq, rq), ("dk_suf", dk, rk), ("dv_suf", dv, rv)):
         res = pu.compare_grad(pu.out_to_f64(got[idx]), r, vs, "bf16", f"huge {name}")
         print(f"       backward {name}: {res}", flush=True)
+
+
+@pytest.mark.parametrize("B,P,S,lo,hi,backward", [
+    (3, 256, 24, 16, 24, True),     # would take the resident pipelined kernels
+    (2, 300, 32, 20, 32, False),    # would take the streamed pipelined kernel
+    (2, 130, 96, 60, 96, False),    # would take the candidate passes
+])
+def test_candidate_spans_beyond_2_31_bytes(pk, B, P, S, lo, hi, backward):
+    """Views with a token stride so large that one candidate's part of q, out and the suffix K/V
+    spans more than 2^31 bytes: the kernels that keep 32-bit offsets within a candidate must not be
+    chosen (or must not wrap); the result is the one of the contiguous call."""
+    import torch
+    Hq, Hkv, D = 8, 2, 128
+    w = gen.custom_workload(f"span_{P}_{S}", B, P, S, lo, hi, Hq, Hkv, D, "bf16", index=1400 + P)
+    inp = gen.make_inputs(w, pad="nan")
+    d = pu.to_device(inp)
+    row = (2 ** 31) // (2 * (S - 1)) + 4096        # elements per token row of the wide buffers
+    row -= row % 8                                  # keeps every row 16-byte aligned
+    assert (S - 1) * row * 2 >= 2 ** 31
+    print(f"[case] wide strides B={B} P={P} S={S} token stride {row} elements seed={w.seed}", flush=True)
+    wide = lambda H: torch.zeros((B, S, row), dtype=torch.bfloat16, device="cuda:0")[:, :, :H * D].view(B, S, H, D)
+    q, ks, vs, out = wide(Hq), wide(Hkv), wide(Hkv), wide(Hq)
+    q.copy_(d["q"]); ks.copy_(d["k_suf"]); vs.copy_(d["v_suf"])
+    out.fill_(float("nan"))
+    lse = torch.empty((B, Hq, S), dtype=torch.float32, device="cuda:0")
+    pk.pskv_attn_fwd(q, ks, vs, d["k_pre"], d["v_pre"], d["suf_len"], out=out, lse=lse, scale=inp.scale)
+    torch.cuda.synchronize()
+    res = pu.compare(pu.out_to_f64(out.contiguous()), pu.oracle_out(inp), inp.suf_len, "bf16", "wide strides")
+    print(f"       {res}", flush=True)
+    if not backward:
+        return
+    dout_host, dout64 = pu.make_dout(inp, w.seed + 7)
+    dout, dq, dk, dv = wide(Hq), wide(Hq), wide(Hkv), wide(Hkv)
+    dout.copy_(torch.from_numpy(dout_host).view(torch.bfloat16).to("cuda:0"))
+    for t in (dq, dk, dv):
+        t.fill_(float("nan"))
+    pk.pskv_attn_bwd(q, ks, vs, d["k_pre"], d["v_pre"], d["suf_len"], out, lse, dout, dq=dq, dk_suf=dk, dv_suf=dv,
+                     scale=inp.scale)
+    torch.cuda.synchronize()
+    rq, rk, rv = pu.oracle_bwd(inp, dout64)
+    valid = np.arange(S)[None, :] < inp.suf_len[:, None]
+    for name, got, r in (("dq", dq, rq), ("dk_suf", dk, rk), ("dv_suf", dv, rv)):
+        pu.compare_grad(pu.out_to_f64(got.contiguous()), r, valid, "bf16", f"wide strides {name}")
