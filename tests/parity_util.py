@@ -159,7 +159,10 @@ def compare_grad(got, ref, valid_rows, dtype, what, few_keys_rows=None):
         std_term = np.full(valid_rows.shape, BF16_TIGHT_STD_GRAD)
         if few_keys_rows is not None:
             std_term[few_keys_rows] = BF16_TIGHT_STD_GRAD_FEW
-        bound = BF16_REL * np.abs(r) + (std_term[valid_rows] * sd)[:, None, None]
+        # + 1e-5: where the exact gradient vanishes altogether (a row that sees one key has
+        # dp = <dout,out> exactly) the kernels leave the fp32 accumulation noise of two 128-term dot
+        # products summed in different orders, about 1e-6
+        bound = BF16_REL * np.abs(r) + (std_term[valid_rows] * sd)[:, None, None] + 1e-5
         res["std_ref"] = sd
         res["tight_ratio"] = float((err / np.maximum(bound, 1e-300)).max())
         # the absolute bar of the forward pass, for tensors whose elements are sums of many terms of

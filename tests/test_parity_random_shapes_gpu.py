@@ -93,3 +93,39 @@ def test_random_multi_shape(pk, case):
     ref, ref_lse = pu.oracle_out_multi(inp, want_lse=True)
     pu.compare_lse(lse.cpu().numpy().astype(np.float64), ref_lse, inp.suf_len, "bf16", w.name)
     pu.compare(pu.out_to_f64(out), ref, inp.suf_len, "bf16", w.name)
+
+
+@pytest.mark.parametrize("B,P,S,Hq,Hkv", [
+    (3, 256, 24, 8, 2),     # resident prefix, pipelined kernel
+    (2, 300, 32, 8, 2),     # streamed prefix
+    (2, 130, 96, 8, 2),     # passes cut out of one candidate
+    (2, 0, 1, 4, 4),        # no prefix, one-token suffixes
+])
+def test_degenerate_lengths(pk, B, P, S, Hq, Hkv):
+    """All candidates empty (everything is padding: exact zeros, lse -inf, zero gradients), then all
+    candidates one token long."""
+    import torch
+    for n in (0, 1):
+        w = gen.custom_workload(f"degenerate_{P}_{S}_{n}", B, P, S, n, n, Hq, Hkv, 128, "bf16", index=1500 + P + n)
+        inp = gen.make_inputs(w, pad="nan")
+        d = pu.to_device(inp)
+        print(f"[case] all lengths {n}: B={B} P={P} S={S} Hq={Hq} Hkv={Hkv} seed={w.seed}", flush=True)
+        lse = torch.full((B, Hq, S), 123.0, device="cuda:0")
+        out = torch.full_like(d["q"], float("nan"))
+        pk.pskv_attn_fwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], out=out, lse=lse,
+                         scale=inp.scale)
+        torch.cuda.synchronize()
+        ref, ref_lse = pu.oracle_out(inp, want_lse=True)
+        pu.compare_lse(lse.cpu().numpy().astype(np.float64), ref_lse, inp.suf_len, "bf16", w.name)
+        pu.compare(pu.out_to_f64(out), ref, inp.suf_len, "bf16", w.name)
+        dout_host, dout64 = pu.make_dout(inp, w.seed + 7)
+        dout = torch.from_numpy(dout_host).view(torch.bfloat16).to("cuda:0")
+        dq, dk, dv = pk.pskv_attn_bwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], out, lse, dout,
+                                      scale=inp.scale)
+        torch.cuda.synchronize()
+        rq, rk, rv = pu.oracle_bwd(inp, dout64)
+        valid = np.arange(S)[None, :] < inp.suf_len[:, None]
+        few = (P + np.arange(S)[None, :] + 1 < pu.FEW_KEYS) & valid
+        for name, got, r in (("dq", dq, rq), ("dk_suf", dk, rk), ("dv_suf", dv, rv)):
+            pu.compare_grad(pu.out_to_f64(got), r, valid, "bf16", f"{w.name} {name}",
+                            few_keys_rows=few if name == "dq" else None)
