@@ -62,13 +62,14 @@ __device__ inline bf16x8 as_bf16x8(uintx4 v)
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// a * b with the rule that zero times anything, infinities and NaN included, is zero.
-__device__ inline float mul_zero_wins(float a, float b)
-{
-    float r;
-    asm("v_mul_legacy_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-    return r;
-}
+// a * b with the rule that zero times anything, infinities and NaN included, is zero
+// (v_mul_legacy_f32).  Bound to the compiler's own intrinsic rather than written as an inline
+// instruction: the operands are matrix-core results, and the wait states a vector instruction
+// needs after the matrix instruction that produced its input are inserted by the compiler only
+// for instructions it emits itself - an inline one too close to the last matrix instruction
+// reads the accumulator before it is written.
+extern "C" __device__ float pskv_fmul_legacy(float, float) __asm("llvm.amdgcn.fmul.legacy");
+__device__ inline float mul_zero_wins(float a, float b) { return pskv_fmul_legacy(a, b); }
 
 __device__ inline unsigned pack_bf16(float lo, float hi)
 {
