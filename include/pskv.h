@@ -17,7 +17,8 @@
  *
  * All pointers except the params struct and the returned strings are DEVICE pointers owned
  * by the caller.  The library allocates, frees and retains no device memory and keeps no
- * state between calls.  Work is enqueued on the given stream and the call returns without
+ * state between calls apart from a one-time set-up per device (compute-unit count, LDS limits
+ * of its kernels), done at the first call on that device.  Work is enqueued on the given stream and the call returns without
  * synchronising; suf_len is read on the device.  Inputs must not alias the outputs.
  * No exception crosses this boundary: every failure is a status code, with a thread-local
  * detail string available from pskv_last_error().  Validation happens on the host before

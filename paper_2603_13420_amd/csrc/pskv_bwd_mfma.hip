@@ -765,23 +765,19 @@ hipError_t launch_bwd_dkv_mfma(const BwdArgs &g, hipStream_t stream)
 
 hipError_t launch_bwd_dq_mfma(const BwdArgs &g, hipStream_t stream)
 {
-    static int num_cu = 0;
-    if (num_cu == 0) {
-        int dev = 0, n = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess)
-            e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(bwd_dq_mfma_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kBwdLdsBytes);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(bwd_dq_resident_kernel),
+    static int cu_by_device[kMaxDevices] = {};
+    hipError_t e;
+    const int num_cu = device_setup_once(cu_by_device, e, [] {
+        hipError_t s = hipFuncSetAttribute(reinterpret_cast<const void *>(bwd_dq_mfma_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kBwdLdsBytes);
+        if (s == hipSuccess)
+            s = hipFuncSetAttribute(reinterpret_cast<const void *>(bwd_dq_resident_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
                                     2 * kDqMaxTiles * kTileBytes + kNW * kScrBytes);
-        if (e != hipSuccess)
-            return e;
-        num_cu = n > 0 ? n : 256;
-    }
+        return s;
+    });
+    if (num_cu == 0)
+        return e;
     const Args &a = g.f;
     const long long rows = (long long)a.C * a.S * a.G;
     // Short prefixes stay resident in LDS (the split of the workgroups over the (instruction, KV

@@ -88,4 +88,32 @@ bool resident_supported(const Args &a);
 hipError_t launch_resident(const Args &a, hipStream_t stream);
 hipError_t launch_stream(const Args &a, hipStream_t stream);
 
+// One-time set-up per device and source file: `slot` is that file's table of compute-unit counts
+// by device number (zero = not set up yet), `setup(dev)` raises the LDS limits of the file's
+// kernels on the current device.  Returns the current device's compute-unit count, 0 with e set
+// on failure.  (Two host threads racing through the first call do the same set-up twice.)
+constexpr int kMaxDevices = 64;
+template <typename F>
+inline int device_setup_once(int (&slot)[kMaxDevices], hipError_t &e, F setup)
+{
+    int dev = 0;
+    e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return 0;
+    if (dev < 0 || dev >= kMaxDevices) {
+        e = hipErrorInvalidDevice;
+        return 0;
+    }
+    if (slot[dev] == 0) {
+        int n = 0;
+        e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e == hipSuccess)
+            e = setup();
+        if (e != hipSuccess)
+            return 0;
+        slot[dev] = n > 0 ? n : 256;
+    }
+    return slot[dev];
+}
+
 } // namespace pskv

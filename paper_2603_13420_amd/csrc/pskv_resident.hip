@@ -293,23 +293,19 @@ bool resident_supported(const Args &a)
 
 hipError_t launch_resident(const Args &a, hipStream_t stream)
 {
-    static int num_cu = 0;
-    if (num_cu == 0) {
-        int dev = 0, n = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess)
-            e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+    static int cu_by_device[kMaxDevices] = {};
+    hipError_t e;
+    const int num_cu = device_setup_once(cu_by_device, e, [] {
         const int max_lds = 2 * kMaxTiles * kTileBytes + kNW * kScrBytes;
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(resident_general_kernel),
+        hipError_t s = hipFuncSetAttribute(reinterpret_cast<const void *>(resident_general_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
+        if (s == hipSuccess)
+            s = hipFuncSetAttribute(reinterpret_cast<const void *>(resident_pipelined_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(resident_pipelined_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, max_lds);
-        if (e != hipSuccess)
-            return e;
-        num_cu = n > 0 ? n : 256;
-    }
+        return s;
+    });
+    if (num_cu == 0)
+        return e;
     const int max_tiles = (a.P + kTileKeys - 1) / kTileKeys;
     const long long rows = (long long)a.C * a.S * a.G; // stacked rows of one virtual head
     const long long nblocks = (rows + kBlockRows - 1) / kBlockRows;

@@ -735,30 +735,21 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
 
 int device_cu_count(hipError_t &e)
 {
-    static int num_cu = 0;
-    e = hipSuccess;
-    if (num_cu == 0) {
-        int dev = 0, n = 0;
-        e = hipGetDevice(&dev);
-        if (e == hipSuccess)
-            e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(stream_general_kernel),
+    static int cu_by_device[kMaxDevices] = {};
+    return device_setup_once(cu_by_device, e, [] {
+        hipError_t s = hipFuncSetAttribute(reinterpret_cast<const void *>(stream_general_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (s == hipSuccess)
+            s = hipFuncSetAttribute(reinterpret_cast<const void *>(stream_pipelined_kernel<true>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(stream_pipelined_kernel<true>),
+        if (s == hipSuccess)
+            s = hipFuncSetAttribute(reinterpret_cast<const void *>(stream_pipelined_kernel<false>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(stream_pipelined_kernel<false>),
+        if (s == hipSuccess)
+            s = hipFuncSetAttribute(reinterpret_cast<const void *>(stream_candidate_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(stream_candidate_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (e != hipSuccess)
-            return 0;
-        num_cu = n > 0 ? n : 256;
-    }
-    return num_cu;
+        return s;
+    });
 }
 
 } // namespace
