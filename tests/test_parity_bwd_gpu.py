@@ -5,7 +5,6 @@ would in use; padded rows of every input, dout included, are NaN-poisoned."""
 import numpy as np
 import pytest
 
-from oracle import pskv_oracle as orc
 from paper_2603_13420_amd import inputs as gen
 import parity_util as pu
 
@@ -41,11 +40,7 @@ def run_bwd(pk, inp, impl="auto", what=""):
     pk.pskv_attn_bwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], out, lse, dout,
                      dq=dq, dk_suf=dk, dv_suf=dv, impl=impl, scale=inp.scale)
     torch.cuda.synchronize()
-    dout64 = np.nan_to_num(dout64, nan=0.0)     # the oracle ignores padded rows; give it finite numbers there
-    P = w.P
-    kp = inp.k_pre if P > 0 else np.zeros((0, w.Hkv, w.D), dtype=inp.q.dtype)
-    vp = inp.v_pre if P > 0 else np.zeros((0, w.Hkv, w.D), dtype=inp.q.dtype)
-    rq, rk, rv = orc.attn_bwd(inp.q, inp.k_suf, inp.v_suf, kp, vp, inp.suf_len, dout64, inp.scale, w.dtype)
+    rq, rk, rv = pu.oracle_bwd(inp, dout64)     # exact gradients with their element-wise error bounds
     valid = np.arange(w.S)[None, :] < inp.suf_len[:, None]
     res = {n: compare_grad(pu.out_to_f64(g), r, valid, w.dtype, f"{what or w.name} {n}")
            for n, g, r in (("dq", dq, rq), ("dk_suf", dk, rk), ("dv_suf", dv, rv))}
@@ -88,8 +83,7 @@ def test_bwd_headline_shape_sampled(pk):
     torch.cuda.synchronize()
     cand = np.array(sorted({0, 1, w.B // 2, w.B - 1, int(np.argmin(inp.suf_len)), int(np.argmax(inp.suf_len))}))
     sub = inp.take(cand)
-    rq, rk, rv = orc.attn_bwd(sub.q, sub.k_suf, sub.v_suf, sub.k_pre, sub.v_pre, sub.suf_len,
-                              np.nan_to_num(dout64[cand], nan=0.0), sub.scale, w.dtype)
+    rq, rk, rv = pu.oracle_bwd(sub, dout64[cand])
     sel = torch.from_numpy(cand).to("cuda:0")
     valid = np.arange(w.S)[None, :] < sub.suf_len[:, None]
     for n, gt, r in (("dq", dq, rq), ("dk_suf", dk, rk), ("dv_suf", dv, rv)):

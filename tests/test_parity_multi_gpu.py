@@ -120,7 +120,6 @@ def test_multi_named_workloads_full_size(pk, name):
 # ------------------------------------------------------------------------------------------
 def run_multi_bwd(pk, inp, impl, what=""):
     import torch
-    from oracle import pskv_oracle as orc
     d = pu.to_device_multi(inp)
     w = inp.w
     print(f"[case] bwd {what or w.name} impl={impl} Np={w.Np} C={w.C} P={w.P} pre_len={inp.pre_len.tolist()[:8]} "
@@ -136,8 +135,7 @@ def run_multi_bwd(pk, inp, impl, what=""):
     pk.pskv_attn_bwd_multi(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["pre_len"], d["suf_len"], out, lse,
                            dout, dq=dq, dk_suf=dk, dv_suf=dv, impl=impl, scale=inp.scale)
     torch.cuda.synchronize()
-    rq, rk, rv = orc.attn_bwd_multi(inp.q, inp.k_suf, inp.v_suf, inp.k_pre, inp.v_pre, inp.pre_len, inp.suf_len,
-                                    np.nan_to_num(dout64, nan=0.0), inp.scale, w.dtype)
+    rq, rk, rv = pu.oracle_bwd_multi(inp, dout64)   # exact gradients with their element-wise error bounds
     valid = np.arange(w.S)[None, :] < inp.suf_len[:, None]
     res = {n: pu.compare_grad(pu.out_to_f64(g), r, valid, w.dtype, f"{what or w.name} {n}")
            for n, g, r in (("dq", dq, rq), ("dk_suf", dk, rk), ("dv_suf", dv, rv))}

@@ -47,7 +47,7 @@ def test_random_shape(pk, case):
     torch.cuda.synchronize()
     ref, ref_lse = pu.oracle_out(inp, want_lse=True)
     pu.compare_lse(lse.cpu().numpy().astype(np.float64), ref_lse, inp.suf_len, "bf16", w.name)
-    pu.compare(pu.out_to_f64(out), ref, inp.suf_len, "bf16", w.name)
+    print("      ", pu.compare(pu.out_to_f64(out), ref, inp.suf_len, "bf16", w.name), flush=True)
     if case % 2:
         return
     dout_host, dout64 = pu.make_dout(inp, w.seed + 7)
@@ -58,10 +58,8 @@ def test_random_shape(pk, case):
     # the oracle differentiates the exact forward pass; the kernels are handed the rounded `out`
     rq, rk, rv = pu.oracle_bwd(inp, dout64)
     valid = np.arange(S)[None, :] < inp.suf_len[:, None]
-    few = (P + np.arange(S)[None, :] + 1 < pu.FEW_KEYS) & valid   # rows that see fewer than FEW_KEYS keys
     for name, got, r in (("dq", dq, rq), ("dk_suf", dk, rk), ("dv_suf", dv, rv)):
-        pu.compare_grad(pu.out_to_f64(got), r, valid, "bf16", f"{w.name} {name}",
-                        few_keys_rows=few if name == "dq" else None)
+        print("      ", name, pu.compare_grad(pu.out_to_f64(got), r, valid, "bf16", f"{w.name} {name}"), flush=True)
 
 
 def draw_multi_shape(case: int):
@@ -125,7 +123,5 @@ def test_degenerate_lengths(pk, B, P, S, Hq, Hkv):
         torch.cuda.synchronize()
         rq, rk, rv = pu.oracle_bwd(inp, dout64)
         valid = np.arange(S)[None, :] < inp.suf_len[:, None]
-        few = (P + np.arange(S)[None, :] + 1 < pu.FEW_KEYS) & valid
         for name, got, r in (("dq", dq, rq), ("dk_suf", dk, rk), ("dv_suf", dv, rv)):
-            pu.compare_grad(pu.out_to_f64(got), r, valid, "bf16", f"{w.name} {name}",
-                            few_keys_rows=few if name == "dq" else None)
+            pu.compare_grad(pu.out_to_f64(got), r, valid, "bf16", f"{w.name} {name}")
