@@ -333,13 +333,18 @@ def main():
     # launches are queued back to back, so the event span divided by the launch count is the
     # average duration of one launch (plus the idle gap between two launches, if any).
     kern_ms = ev_ms
-    # For comparison, launches timed one at a time by the library's own event-bracketed helper.
+    # For comparison, launches timed one at a time, each between its own pair of events.
     isolated_ms = None
     if not multi_call:
-        per_set = [pk.pskv_attn_fwd_timed(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"],
-                                          d["suf_len"], d["out"], impl=args.impl, scale=inp.scale, iters=1,
-                                          stream=stream)
-                   for _ in range(max(1, min(20, args.steps // nsets))) for d in sets]
+        per_set = []
+        for _ in range(max(1, min(20, args.steps // nsets))):
+            for i in range(nsets):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                prepared[i]()
+                e1.record()
+                e1.synchronize()
+                per_set.append(e0.elapsed_time(e1))
         isolated_ms = float(np.mean(per_set))
 
     # quick self-check of the timed configuration on a few candidates (not timed)

@@ -18,11 +18,20 @@
  * All pointers except the params struct and the returned strings are DEVICE pointers owned
  * by the caller.  The library allocates, frees and retains no device memory and keeps no
  * state between calls apart from a one-time set-up per device (compute-unit count, LDS limits
- * of its kernels), done at the first call on that device.  Work is enqueued on the given stream and the call returns without
- * synchronising; suf_len is read on the device.  Inputs must not alias the outputs.
+ * of its kernels), done at the first call on that device and
+ * safe against host threads that make that first call at the same time.  The stream must belong
+ * to the device that is current when the call is made.  Work is enqueued on the given stream and
+ * the call returns without synchronising (no entry point synchronises, creates events or waits);
+ * suf_len is read on the device.  No part of an input may share a byte with an output, nor two
+ * outputs with each other: address ranges are compared, not just first bytes; column slices of one
+ * fused buffer (same token stride, per-token spans side by side) are recognised as disjoint, any
+ * other pair of tensors whose ranges meet is refused.
  * No exception crosses this boundary: every failure is a status code, with a thread-local
  * detail string available from pskv_last_error().  Validation happens on the host before
- * anything is launched; a call that returns an error has launched nothing.
+ * anything is launched: a call that returns INVALID_ARG, UNSUPPORTED or WORKSPACE has launched
+ * nothing.  PSKV_ERR_HIP reports what the HIP runtime said about the library's own launch (not
+ * an error left behind by earlier, unrelated calls); the backward calls launch two kernels, so
+ * there the first may already be enqueued when the second is refused.
  */
 #ifndef PSKV_H
 #define PSKV_H
@@ -38,16 +47,17 @@ typedef enum {
     PSKV_OK = 0,
     PSKV_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, Hq % Hkv != 0, misaligned pointer/stride */
     PSKV_ERR_UNSUPPORTED = 2, /* shape or dtype outside what the kernels cover */
-    PSKV_ERR_WORKSPACE = 3,   /* workspace smaller than pskv_attn_fwd_workspace_bytes() */
+    PSKV_ERR_WORKSPACE = 3,   /* a workspace that cannot be used (misaligned, overlapping a tensor) */
     PSKV_ERR_HIP = 4          /* the HIP runtime refused a launch or query */
 } pskv_status;
 
 typedef enum {
-    PSKV_DTYPE_F32 = 0, /* q/k/v/out are float; fp32 arithmetic throughout */
+    PSKV_DTYPE_F32 = 0, /* q/k/v/out are float; fp64 arithmetic on the vector ALU, results rounded to fp32 once */
     PSKV_DTYPE_BF16 = 1 /* q/k/v/out are bfloat16; bf16 MFMA with fp32 accumulation and fp32 softmax */
 } pskv_dtype;
 
-/* Kernel selection. AUTO picks the MFMA path whenever it covers the problem. */
+/* Kernel selection. AUTO picks the MFMA path whenever it covers the problem; the other two values
+ * exist so that tests and benchmarks can run one problem through both implementations. */
 typedef enum {
     PSKV_IMPL_AUTO = 0,
     PSKV_IMPL_SIMPLE = 1, /* one wavefront per query row, fp32 vector arithmetic; any D <= 256, any dtype */
@@ -128,20 +138,6 @@ pskv_status pskv_attn_fwd(const pskv_attn_params *p,
                           void *out, float *lse,
                           void *workspace, size_t workspace_bytes,
                           void *hip_stream);
-
-/*
- * Timing helper for benchmarks: enqueues `iters` back-to-back pskv_attn_fwd calls on
- * `hip_stream`, bracketed by HIP events recorded on that same stream, waits for the last
- * one and stores the mean duration of one call in *ms_per_call.  Arguments as for
- * pskv_attn_fwd.  This call synchronises the stream.
- */
-pskv_status pskv_attn_fwd_timed(const pskv_attn_params *p,
-                                const void *q, const void *k_suf, const void *v_suf,
-                                const void *k_pre, const void *v_pre,
-                                const int32_t *suf_len,
-                                void *out, float *lse,
-                                void *workspace, size_t workspace_bytes,
-                                void *hip_stream, int iters, float *ms_per_call);
 
 /*
  * Batched multi-instruction form (paper Sec. 4.3, suffix-centric alignment; App. F.1, position

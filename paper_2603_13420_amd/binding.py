@@ -18,7 +18,7 @@ PSKV_IMPL_AUTO, PSKV_IMPL_SIMPLE, PSKV_IMPL_MFMA = 0, 1, 2
 _IMPL = {"auto": PSKV_IMPL_AUTO, "simple": PSKV_IMPL_SIMPLE, "mfma": PSKV_IMPL_MFMA}
 
 EXPORTS = ["pskv_version", "pskv_status_str", "pskv_last_error", "pskv_attn_fwd_workspace_bytes",
-           "pskv_attn_validate", "pskv_attn_fwd", "pskv_attn_fwd_timed",
+           "pskv_attn_validate", "pskv_attn_fwd",
            "pskv_attn_multi_validate", "pskv_attn_fwd_multi", "pskv_attn_bwd", "pskv_attn_bwd_multi",
            "pskv_attn_bwd_workspace_bytes"]
 
@@ -69,8 +69,6 @@ def load():
     fwd_args = [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
     lib.pskv_attn_fwd.restype = ctypes.c_int
     lib.pskv_attn_fwd.argtypes = fwd_args
-    lib.pskv_attn_fwd_timed.restype = ctypes.c_int
-    lib.pskv_attn_fwd_timed.argtypes = fwd_args + [ctypes.c_int, ctypes.POINTER(ctypes.c_float)]
     PM = ctypes.POINTER(pskv_multi_params)
     lib.pskv_attn_multi_validate.restype = ctypes.c_int
     lib.pskv_attn_multi_validate.argtypes = [PM]
@@ -126,6 +124,19 @@ def pskv_attn_fwd_workspace_bytes(p: pskv_attn_params) -> int:
     return n
 
 
+def _stride(t, dim: int, name: str) -> int:
+    """Element stride of dimension `dim` as the C ABI wants it.  The ABI reads 0 as "contiguous", so
+    a real stride of 0 (an expanded view, e.g. one prefix broadcast over the instructions) must not
+    reach it: the kernels would run over the end of the allocation.  A dimension of size 1 has no
+    stride to speak of and is passed as 0."""
+    if t.shape[dim] <= 1:
+        return 0
+    if t.stride(dim) == 0:
+        raise ValueError(f"{name}: dimension {dim} of size {t.shape[dim]} has stride 0 (an expanded view); "
+                         "materialise it with .contiguous()")
+    return t.stride(dim)
+
+
 def _params_from_tensors(q, k_suf, k_pre, out, impl, scale):
     import torch
     B, S, Hq, D = q.shape
@@ -133,13 +144,14 @@ def _params_from_tensors(q, k_suf, k_pre, out, impl, scale):
     P = 0 if k_pre is None else k_pre.shape[0]
     dtype = {torch.float32: "f32", torch.bfloat16: "bf16"}[q.dtype]
     for t in (q, k_suf, out) + (() if k_pre is None else (k_pre,)):
-        if t.stride(-1) != 1:
+        if t.shape[-1] > 1 and t.stride(-1) != 1:
             raise ValueError("innermost dimension must have stride 1")
-    st = dict(q_stride_b=q.stride(0), q_stride_s=q.stride(1), q_stride_h=q.stride(2),
-              ks_stride_b=k_suf.stride(0), ks_stride_s=k_suf.stride(1), ks_stride_h=k_suf.stride(2),
-              o_stride_b=out.stride(0), o_stride_s=out.stride(1), o_stride_h=out.stride(2))
+    st = dict(q_stride_b=_stride(q, 0, "q"), q_stride_s=_stride(q, 1, "q"), q_stride_h=_stride(q, 2, "q"),
+              ks_stride_b=_stride(k_suf, 0, "k_suf"), ks_stride_s=_stride(k_suf, 1, "k_suf"),
+              ks_stride_h=_stride(k_suf, 2, "k_suf"),
+              o_stride_b=_stride(out, 0, "out"), o_stride_s=_stride(out, 1, "out"), o_stride_h=_stride(out, 2, "out"))
     if k_pre is not None and P > 0:
-        st.update(kp_stride_p=k_pre.stride(0), kp_stride_h=k_pre.stride(1))
+        st.update(kp_stride_p=_stride(k_pre, 0, "k_pre"), kp_stride_h=_stride(k_pre, 1, "k_pre"))
     return make_params(B, S, P, Hq, Hkv, D, dtype, impl, scale, **st)
 
 
@@ -220,26 +232,6 @@ class PreparedCall:
             _raise(rc)
 
 
-def pskv_attn_fwd_timed(q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse=None, impl: str = "auto",
-                        scale: float = 0.0, iters: int = 10, stream: Optional[int] = None) -> float:
-    """Mean milliseconds of one call over `iters` back-to-back calls, measured with HIP events
-    on the stream the kernels run on.  Synchronises that stream."""
-    import torch
-    _check_inputs(q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse)
-    p = _params_from_tensors(q, k_suf, k_pre, out, impl, scale)
-    if stream is None:
-        stream = torch.cuda.current_stream(q.device).cuda_stream
-    ms = ctypes.c_float(0.0)
-    with torch.cuda.device(q.device):
-        rc = load().pskv_attn_fwd_timed(ctypes.byref(p), _ptr(q), _ptr(k_suf), _ptr(v_suf),
-                                        _ptr(k_pre), _ptr(v_pre), _ptr(suf_len), _ptr(out),
-                                        _ptr(lse), None, 0, ctypes.c_void_p(stream), int(iters),
-                                        ctypes.byref(ms))
-    if rc != PSKV_OK:
-        _raise(rc)
-    return float(ms.value)
-
-
 def make_multi_params(base: pskv_attn_params, Np: int, kp_stride_n: int = 0) -> pskv_multi_params:
     p = pskv_multi_params()
     p.base = base
@@ -264,7 +256,7 @@ def _multi_setup(q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, out, lse, impl
     # one instruction's prefix has the [P,Hkv,D] form the single-prefix checks know
     _check_inputs(q, k_suf, v_suf, k_pre[0], v_pre[0], suf_len, out, lse)
     base = _params_from_tensors(q, k_suf, k_pre[0], out, impl, scale)
-    return make_multi_params(base, Np, k_pre.stride(0) if Np > 1 else 0)
+    return make_multi_params(base, Np, _stride(k_pre, 0, "k_pre"))
 
 
 def pskv_attn_fwd_multi(q, k_suf, v_suf, k_pre, v_pre, pre_len=None, suf_len=None, out=None, lse=None,
@@ -306,11 +298,14 @@ class PreparedMultiCall:
             _raise(rc)
 
 
-def _bwd_workspace(p, workspace, device):
+def _bwd_workspace(p, workspace, device, own_stream: bool):
     """The scratch tensor to hand to a backward call: the caller's, or a fresh one from torch
-    (workspace=None), or none at all (workspace=False)."""
+    (workspace=None), or none at all (workspace=False).  A fresh one goes back to torch's allocator
+    when the call returns, which is only safe while the kernels run on torch's current stream (the
+    allocator orders reuse by that stream): with a raw stream of the caller's the call does without
+    scratch unless the caller brings a tensor and keeps it alive."""
     import torch
-    if workspace is False:
+    if workspace is False or (workspace is None and own_stream):
         return None, 0
     if workspace is None:
         need = int(load().pskv_attn_bwd_workspace_bytes(ctypes.byref(p)))
@@ -342,7 +337,7 @@ def pskv_attn_bwd(q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse, dout, dq=Non
         if t.shape != k_suf.shape or t.stride() != k_suf.stride() or t.dtype != q.dtype:
             raise ValueError(f"{name} must have the shape, strides and dtype of k_suf")
     p = _params_from_tensors(q, k_suf, k_pre, out, impl, scale)
-    ws, ws_bytes = _bwd_workspace(p, workspace, q.device)
+    ws, ws_bytes = _bwd_workspace(p, workspace, q.device, stream is not None)
     if stream is None:
         stream = torch.cuda.current_stream(q.device).cuda_stream
     with torch.cuda.device(q.device):
@@ -373,7 +368,7 @@ def pskv_attn_bwd_multi(q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, out, ls
     for name, t in (("dk_suf", dk_suf), ("dv_suf", dv_suf)):
         if t.shape != k_suf.shape or t.stride() != k_suf.stride() or t.dtype != q.dtype:
             raise ValueError(f"{name} must have the shape, strides and dtype of k_suf")
-    ws, ws_bytes = _bwd_workspace(p.base, workspace, q.device)
+    ws, ws_bytes = _bwd_workspace(p.base, workspace, q.device, stream is not None)
     if stream is None:
         stream = torch.cuda.current_stream(q.device).cuda_stream
     with torch.cuda.device(q.device):
@@ -383,3 +378,4 @@ def pskv_attn_bwd_multi(q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, out, ls
     if rc != PSKV_OK:
         _raise(rc)
     return dq, dk_suf, dv_suf
+

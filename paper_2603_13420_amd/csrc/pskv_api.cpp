@@ -112,6 +112,62 @@ pskv_status resolve(const pskv_attn_params *p, int np, long long kp_stride_n, ps
 
 bool misaligned(const void *ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15u) != 0; }
 
+// A tensor as a range of addresses: [lo, hi) covers every byte the strides can reach.  When all of
+// its tokens (one position of one candidate: n2 rows of d elements, s2 apart) start on a lattice of
+// pitch bytes from lo - the token stride, which the candidate stride is a multiple of - pitch and the
+// bytes one token spans (foot) are kept too: that is the shape of a column slice of a fused buffer.
+struct Span {
+    uintptr_t lo, hi;
+    const char *name;
+    uintptr_t pitch, foot; // pitch 0: no lattice known
+};
+Span span4(const void *ptr, long long n0, long long s0, long long n1, long long s1, long long n2, long long s2, long long d,
+           int esize, const char *name)
+{
+    if (!ptr || n0 < 1 || n1 < 1 || n2 < 1)
+        return Span{0, 0, name, 0, 0};
+    const long long last = (n0 - 1) * s0 + (n1 - 1) * s1 + (n2 - 1) * s2 + d; // elements up to the end of the last row
+    const uintptr_t lo = reinterpret_cast<uintptr_t>(ptr);
+    Span s{lo, lo + (uintptr_t)last * (uintptr_t)esize, name, 0, 0};
+    const long long foot = (n2 - 1) * s2 + d;
+    if (s1 > 0 && foot <= s1 && (n0 == 1 || s0 % s1 == 0)) {
+        s.pitch = (uintptr_t)s1 * (uintptr_t)esize;
+        s.foot = (uintptr_t)foot * (uintptr_t)esize;
+    }
+    return s;
+}
+// Whether two tensors may share a byte.  Ranges that do not meet share nothing; two column slices of
+// one fused buffer (same token pitch) interleave without sharing a byte when their per-token spans sit
+// side by side inside the pitch.  Anything else whose ranges meet is treated as overlapping.
+bool overlap(const Span &x, const Span &y)
+{
+    if (!(x.lo < y.hi && y.lo < x.hi))
+        return false;
+    if (x.pitch != 0 && x.pitch == y.pitch) {
+        const uintptr_t delta = y.lo >= x.lo ? (y.lo - x.lo) % x.pitch : (x.pitch - (x.lo - y.lo) % x.pitch) % x.pitch;
+        if (x.foot <= delta && delta + y.foot <= x.pitch)
+            return false; // x's tokens fill [0, foot) of every pitch, y's [delta, delta + foot)
+    }
+    return true;
+}
+
+// The address ranges of a problem's tensors (np: prefixes in k_pre / v_pre).
+struct Spans {
+    Span q, ks, vs, kp, vp, out;
+};
+Spans tensor_spans(const pskv::Args &a, int esize, const void *q, const void *ks, const void *vs, const void *kp,
+                   const void *vp, const void *out)
+{
+    Spans s;
+    s.q = span4(q, a.B, a.q_sb, a.S, a.q_ss, a.Hq, a.q_sh, a.D, esize, "q");
+    s.ks = span4(ks, a.B, a.ks_sb, a.S, a.ks_ss, a.Hkv, a.ks_sh, a.D, esize, "k_suf");
+    s.vs = span4(vs, a.B, a.ks_sb, a.S, a.ks_ss, a.Hkv, a.ks_sh, a.D, esize, "v_suf");
+    s.kp = span4(a.P > 0 ? kp : nullptr, a.Np, a.kp_sn, a.P, a.kp_sp, a.Hkv, a.kp_sh, a.D, esize, "k_pre");
+    s.vp = span4(a.P > 0 ? vp : nullptr, a.Np, a.kp_sn, a.P, a.kp_sp, a.Hkv, a.kp_sh, a.D, esize, "v_pre");
+    s.out = span4(out, a.B, a.o_sb, a.S, a.o_ss, a.Hq, a.o_sh, a.D, esize, "out");
+    return s;
+}
+
 // Everything the two forward entry points share: checks, then one launch on the caller's stream.
 pskv_status launch(const pskv_attn_params *p, int np, long long kp_stride_n, const void *q, const void *k_suf,
                    const void *v_suf, const void *k_pre, const void *v_pre, const int32_t *pre_len,
@@ -133,8 +189,19 @@ pskv_status launch(const pskv_attn_params *p, int np, long long kp_stride_n, con
     if ((reinterpret_cast<uintptr_t>(suf_len) & 3u) || (reinterpret_cast<uintptr_t>(lse) & 3u) ||
         (reinterpret_cast<uintptr_t>(pre_len) & 3u))
         return fail(PSKV_ERR_INVALID_ARG, "suf_len, pre_len and lse must be 4-byte aligned");
-    if (out == q || out == k_suf || out == v_suf || out == k_pre || out == v_pre)
-        return fail(PSKV_ERR_INVALID_ARG, "out must not alias an input");
+    {
+        const int esize = p->dtype == PSKV_DTYPE_BF16 ? 2 : 4;
+        const Spans sp = tensor_spans(a, esize, q, k_suf, v_suf, k_pre, v_pre, out);
+        const Span lse_span = span4(lse, 1, 0, 1, 0, 1, 0, (long long)a.B * a.Hq * a.S, 4, "lse");
+        for (const Span &in : {sp.q, sp.ks, sp.vs, sp.kp, sp.vp}) {
+            if (overlap(sp.out, in))
+                return fail(PSKV_ERR_INVALID_ARG, "out overlaps %s: an output must not alias an input", in.name);
+            if (overlap(lse_span, in))
+                return fail(PSKV_ERR_INVALID_ARG, "lse overlaps %s: an output must not alias an input", in.name);
+        }
+        if (overlap(sp.out, lse_span))
+            return fail(PSKV_ERR_INVALID_ARG, "out overlaps lse");
+    }
 
     a.q = q; a.ks = k_suf; a.vs = v_suf; a.kp = k_pre; a.vp = v_pre;
     a.len = suf_len; a.plen = pre_len; a.out = out; a.lse = lse;
@@ -158,7 +225,7 @@ const char *pskv_status_str(pskv_status s)
     case PSKV_OK: return "ok";
     case PSKV_ERR_INVALID_ARG: return "invalid argument";
     case PSKV_ERR_UNSUPPORTED: return "unsupported shape or dtype";
-    case PSKV_ERR_WORKSPACE: return "workspace too small";
+    case PSKV_ERR_WORKSPACE: return "unusable workspace or scratch too small";
     case PSKV_ERR_HIP: return "HIP runtime error";
     }
     return "unknown status";
@@ -266,15 +333,23 @@ static pskv_status launch_bwd(const pskv_attn_params *p, int np, int64_t kp_stri
     if ((reinterpret_cast<uintptr_t>(suf_len) & 3u) || (reinterpret_cast<uintptr_t>(lse) & 3u) ||
         (reinterpret_cast<uintptr_t>(pre_len) & 3u))
         return fail(PSKV_ERR_INVALID_ARG, "suf_len, pre_len and lse must be 4-byte aligned");
-    const void *ins[] = {q, k_suf, v_suf, k_pre, v_pre, out, dout, lse};
-    void *outs[] = {dq, dk_suf, dv_suf};
+    const int esize = p->dtype == PSKV_DTYPE_BF16 ? 2 : 4;
+    const Spans sp = tensor_spans(a, esize, q, k_suf, v_suf, k_pre, v_pre, out);
+    const Span ins[] = {sp.q, sp.ks, sp.vs, sp.kp, sp.vp, sp.out,
+                        span4(dout, a.B, a.o_sb, a.S, a.o_ss, a.Hq, a.o_sh, a.D, esize, "dout"),
+                        span4(lse, 1, 0, 1, 0, 1, 0, (long long)a.B * a.Hq * a.S, 4, "lse")};
+    const Span outs[] = {span4(dq, a.B, a.q_sb, a.S, a.q_ss, a.Hq, a.q_sh, a.D, esize, "dq"),
+                         span4(dk_suf, a.B, a.ks_sb, a.S, a.ks_ss, a.Hkv, a.ks_sh, a.D, esize, "dk_suf"),
+                         span4(dv_suf, a.B, a.ks_sb, a.S, a.ks_ss, a.Hkv, a.ks_sh, a.D, esize, "dv_suf")};
     for (int x = 0; x < 3; ++x) {
-        for (const void *in : ins)
-            if (outs[x] == in)
-                return fail(PSKV_ERR_INVALID_ARG, "a gradient output must not alias an input");
+        for (const Span &in : ins)
+            if (overlap(outs[x], in))
+                return fail(PSKV_ERR_INVALID_ARG, "%s overlaps %s: a gradient output must not alias an input", outs[x].name,
+                            in.name);
         for (int y = x + 1; y < 3; ++y)
-            if (outs[x] == outs[y])
-                return fail(PSKV_ERR_INVALID_ARG, "gradient outputs must not alias one another");
+            if (overlap(outs[x], outs[y]))
+                return fail(PSKV_ERR_INVALID_ARG, "%s overlaps %s: gradient outputs must not alias one another",
+                            outs[x].name, outs[y].name);
     }
     a.q = q; a.ks = k_suf; a.vs = v_suf; a.kp = k_pre; a.vp = v_pre;
     a.len = suf_len;
@@ -288,13 +363,14 @@ static pskv_status launch_bwd(const pskv_attn_params *p, int np, int64_t kp_stri
     g.delta = nullptr;
     if (dq_mfma && workspace && workspace_bytes >= delta_bytes) {
         if (reinterpret_cast<uintptr_t>(workspace) & 15u)
-            return fail(PSKV_ERR_INVALID_ARG, "workspace %p is not 16-byte aligned", workspace);
-        for (const void *in : ins)
-            if (workspace == in)
-                return fail(PSKV_ERR_INVALID_ARG, "workspace must not alias an input");
-        for (void *o : outs)
-            if (workspace == o)
-                return fail(PSKV_ERR_INVALID_ARG, "workspace must not alias an output");
+            return fail(PSKV_ERR_WORKSPACE, "workspace %p is not 16-byte aligned", workspace);
+        const Span ws = span4(workspace, 1, 0, 1, 0, 1, 0, (long long)delta_bytes, 1, "workspace");
+        for (const Span &in : ins)
+            if (overlap(ws, in))
+                return fail(PSKV_ERR_WORKSPACE, "workspace overlaps %s", in.name);
+        for (const Span &o : outs)
+            if (overlap(ws, o))
+                return fail(PSKV_ERR_WORKSPACE, "workspace overlaps %s", o.name);
         g.delta = static_cast<float *>(workspace);
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -327,42 +403,6 @@ pskv_status pskv_attn_bwd_multi(const pskv_multi_params *p, const void *q, const
         return fail(PSKV_ERR_INVALID_ARG, "reserved field must be 0");
     return launch_bwd(&p->base, p->Np, p->kp_stride_n, q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, out, lse, dout, dq,
                       dk_suf, dv_suf, workspace, workspace_bytes, hip_stream);
-}
-
-pskv_status pskv_attn_fwd_timed(const pskv_attn_params *p, const void *q, const void *k_suf,
-                                const void *v_suf, const void *k_pre, const void *v_pre,
-                                const int32_t *suf_len, void *out, float *lse, void *workspace,
-                                size_t workspace_bytes, void *hip_stream, int iters,
-                                float *ms_per_call)
-{
-    if (iters < 1 || !ms_per_call)
-        return fail(PSKV_ERR_INVALID_ARG, "iters must be >= 1 and ms_per_call non-NULL");
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    hipEvent_t t0 = nullptr, t1 = nullptr;
-    if (hipEventCreate(&t0) != hipSuccess || hipEventCreate(&t1) != hipSuccess) {
-        if (t0) (void)hipEventDestroy(t0);
-        return fail(PSKV_ERR_HIP, "hipEventCreate failed");
-    }
-    pskv_status s = PSKV_OK;
-    hipError_t e = hipEventRecord(t0, stream);
-    for (int it = 0; it < iters && s == PSKV_OK && e == hipSuccess; ++it)
-        s = pskv_attn_fwd(p, q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse, workspace,
-                          workspace_bytes, hip_stream);
-    if (e == hipSuccess)
-        e = hipEventRecord(t1, stream);
-    if (e == hipSuccess)
-        e = hipEventSynchronize(t1);
-    float ms = 0.f;
-    if (e == hipSuccess)
-        e = hipEventElapsedTime(&ms, t0, t1);
-    (void)hipEventDestroy(t0);
-    (void)hipEventDestroy(t1);
-    if (s != PSKV_OK)
-        return s;
-    if (e != hipSuccess)
-        return fail(PSKV_ERR_HIP, "event timing failed: %s", hipGetErrorString(e));
-    *ms_per_call = ms / (float)iters;
-    return PSKV_OK;
 }
 
 } // extern "C"

@@ -755,17 +755,16 @@ hipError_t launch_bwd_dkv_mfma(const BwdArgs &g, hipStream_t stream)
     const long long nunits = (long long)a.B * a.Hkv * nkt;
     const unsigned grid = (unsigned)((2 * nunits + kDkvWaves - 1) / kDkvWaves);
     if (g.delta)
-        hipLaunchKernelGGL(bwd_dkv_mfma_kernel<true>, dim3(grid), dim3(kDkvWaves * 64), kDkvLdsBytes, stream, g, (int)nunits,
+        return launch_kernel(bwd_dkv_mfma_kernel<true>, dim3(grid), dim3(kDkvWaves * 64), kDkvLdsBytes, stream, g, (int)nunits,
                            nkt);
     else
-        hipLaunchKernelGGL(bwd_dkv_mfma_kernel<false>, dim3(grid), dim3(kDkvWaves * 64), kDkvLdsBytes, stream, g, (int)nunits,
+        return launch_kernel(bwd_dkv_mfma_kernel<false>, dim3(grid), dim3(kDkvWaves * 64), kDkvLdsBytes, stream, g, (int)nunits,
                            nkt);
-    return hipGetLastError();
 }
 
 hipError_t launch_bwd_dq_mfma(const BwdArgs &g, hipStream_t stream)
 {
-    static int cu_by_device[kMaxDevices] = {};
+    static DeviceSlots cu_by_device;
     hipError_t e;
     const int num_cu = device_setup_once(cu_by_device, e, [] {
         hipError_t s = hipFuncSetAttribute(reinterpret_cast<const void *>(bwd_dq_mfma_kernel),
@@ -793,15 +792,13 @@ hipError_t launch_bwd_dq_mfma(const BwdArgs &g, hipStream_t stream)
         if (per_vh > useful)
             per_vh = useful;
         const size_t lds = (size_t)2 * max_tiles * kTileBytes + kNW * kScrBytes;
-        hipLaunchKernelGGL(bwd_dq_resident_kernel, dim3((unsigned)(per_vh * vh_slots)), dim3(kNW * 64), lds, stream, g,
+        return launch_kernel(bwd_dq_resident_kernel, dim3((unsigned)(per_vh * vh_slots)), dim3(kNW * 64), lds, stream, g,
                            (int)per_vh, (int)vh_slots, max_tiles);
-        return hipGetLastError();
     }
     const long long npasses = ((rows + kBwdPassRows - 1) / kBwdPassRows) * a.Np * a.Hkv;
     // two workgroups fit a compute unit's LDS; registers allow one, so one per compute unit
     const unsigned grid = (unsigned)(npasses < num_cu ? npasses : num_cu);
-    hipLaunchKernelGGL(bwd_dq_mfma_kernel, dim3(grid), dim3(kNW * 64), kBwdLdsBytes, stream, g, (int)npasses);
-    return hipGetLastError();
+    return launch_kernel(bwd_dq_mfma_kernel, dim3(grid), dim3(kNW * 64), kBwdLdsBytes, stream, g, (int)npasses);
 }
 
 } // namespace pskv

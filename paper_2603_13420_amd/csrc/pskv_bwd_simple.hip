@@ -234,10 +234,9 @@ hipError_t launch_bwd_dq_simple(const BwdArgs &g, int dtype, hipStream_t stream)
     const long long rows = (long long)a.B * a.S * a.Hq;
     const size_t lds = bwd_simple_lds_bytes(a, dtype);
     if (dtype == 0)
-        hipLaunchKernelGGL((bwd_dq_kernel<float, double>), dim3((unsigned)rows), dim3(64), lds, stream, g);
+        return launch_kernel((bwd_dq_kernel<float, double>), dim3((unsigned)rows), dim3(64), lds, stream, g);
     else
-        hipLaunchKernelGGL((bwd_dq_kernel<unsigned short, float>), dim3((unsigned)rows), dim3(64), lds, stream, g);
-    return hipGetLastError();
+        return launch_kernel((bwd_dq_kernel<unsigned short, float>), dim3((unsigned)rows), dim3(64), lds, stream, g);
 }
 
 hipError_t launch_bwd_dkv_simple(const BwdArgs &g, int dtype, hipStream_t stream)
@@ -246,10 +245,9 @@ hipError_t launch_bwd_dkv_simple(const BwdArgs &g, int dtype, hipStream_t stream
     const long long rows = (long long)a.B * a.S * a.Hkv;
     const size_t lds = bwd_dkv_lds_bytes(a, dtype);
     if (dtype == 0)
-        hipLaunchKernelGGL((bwd_dkv_kernel<float, double>), dim3((unsigned)rows), dim3(64), lds, stream, g);
+        return launch_kernel((bwd_dkv_kernel<float, double>), dim3((unsigned)rows), dim3(64), lds, stream, g);
     else
-        hipLaunchKernelGGL((bwd_dkv_kernel<unsigned short, float>), dim3((unsigned)rows), dim3(64), lds, stream, g);
-    return hipGetLastError();
+        return launch_kernel((bwd_dkv_kernel<unsigned short, float>), dim3((unsigned)rows), dim3(64), lds, stream, g);
 }
 
 } // namespace pskv

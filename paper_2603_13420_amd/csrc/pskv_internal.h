@@ -3,6 +3,9 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <mutex>
+#include <tuple>
+#include <utility>
 
 namespace pskv {
 
@@ -88,13 +91,18 @@ bool resident_supported(const Args &a);
 hipError_t launch_resident(const Args &a, hipStream_t stream);
 hipError_t launch_stream(const Args &a, hipStream_t stream);
 
-// One-time set-up per device and source file: `slot` is that file's table of compute-unit counts
-// by device number (zero = not set up yet), `setup(dev)` raises the LDS limits of the file's
+// One-time set-up per device and source file: `slots` is that file's table of compute-unit
+// counts by device number (zero = not set up yet), `setup()` raises the LDS limits of the file's
 // kernels on the current device.  Returns the current device's compute-unit count, 0 with e set
-// on failure.  (Two host threads racing through the first call do the same set-up twice.)
+// on failure (the next call tries again).  Host threads that meet in the first call on a device
+// are serialised by the table's mutex: one of them does the set-up, the others find it done.
 constexpr int kMaxDevices = 64;
+struct DeviceSlots {
+    std::mutex mu;
+    int cu[kMaxDevices] = {};
+};
 template <typename F>
-inline int device_setup_once(int (&slot)[kMaxDevices], hipError_t &e, F setup)
+inline int device_setup_once(DeviceSlots &slots, hipError_t &e, F setup)
 {
     int dev = 0;
     e = hipGetDevice(&dev);
@@ -104,16 +112,35 @@ inline int device_setup_once(int (&slot)[kMaxDevices], hipError_t &e, F setup)
         e = hipErrorInvalidDevice;
         return 0;
     }
-    if (slot[dev] == 0) {
+    std::lock_guard<std::mutex> guard(slots.mu);
+    if (slots.cu[dev] == 0) {
         int n = 0;
         e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
         if (e == hipSuccess)
             e = setup();
         if (e != hipSuccess)
             return 0;
-        slot[dev] = n > 0 ? n : 256;
+        slots.cu[dev] = n > 0 ? n : 256;
     }
-    return slot[dev];
+    return slots.cu[dev];
+}
+
+// Launches `kernel` and returns the status of THIS launch (hipLaunchKernel reports it directly), so
+// that an error left behind by earlier, unrelated HIP activity of the caller is neither picked up
+// nor cleared, as reading the thread's last-error slot after the launch would.
+template <typename... KArgs, size_t... I>
+inline hipError_t launch_kernel_impl(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t stream,
+                                     std::tuple<KArgs...> &vals, std::index_sequence<I...>)
+{
+    void *ptrs[] = {static_cast<void *>(&std::get<I>(vals))...};
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, ptrs, lds, stream);
+}
+template <typename... KArgs, typename... Args>
+inline hipError_t launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t stream, Args... args)
+{
+    static_assert(sizeof...(KArgs) == sizeof...(Args), "argument count does not match the kernel's");
+    std::tuple<KArgs...> vals{static_cast<KArgs>(args)...};
+    return launch_kernel_impl(kernel, grid, block, lds, stream, vals, std::index_sequence_for<KArgs...>{});
 }
 
 } // namespace pskv

@@ -293,7 +293,7 @@ bool resident_supported(const Args &a)
 
 hipError_t launch_resident(const Args &a, hipStream_t stream)
 {
-    static int cu_by_device[kMaxDevices] = {};
+    static DeviceSlots cu_by_device;
     hipError_t e;
     const int num_cu = device_setup_once(cu_by_device, e, [] {
         const int max_lds = 2 * kMaxTiles * kTileBytes + kNW * kScrBytes;
@@ -323,12 +323,11 @@ hipError_t launch_resident(const Args &a, hipStream_t stream)
     const bool pipelined = ((long long)a.S * a.G) % kBlockRows == 0 && a.S <= kTileKeys && max_tiles >= 3 &&
                            block_offsets_fit(a);
     if (pipelined)
-        hipLaunchKernelGGL(resident_pipelined_kernel, dim3(grid), dim3(kNW * 64), lds, stream, a, (int)per_vh,
+        return launch_kernel(resident_pipelined_kernel, dim3(grid), dim3(kNW * 64), lds, stream, a, (int)per_vh,
                            (int)vh_slots, max_tiles);
     else
-        hipLaunchKernelGGL(resident_general_kernel, dim3(grid), dim3(kNW * 64), lds, stream, a, (int)per_vh,
+        return launch_kernel(resident_general_kernel, dim3(grid), dim3(kNW * 64), lds, stream, a, (int)per_vh,
                            (int)vh_slots, max_tiles);
-    return hipGetLastError();
 }
 
 } // namespace pskv

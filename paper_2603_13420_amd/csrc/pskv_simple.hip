@@ -147,10 +147,9 @@ hipError_t launch_simple(const Args &a, int dtype, hipStream_t stream)
     const dim3 grid((unsigned)rows), block(64);
     const size_t lds = simple_lds_bytes(a, dtype);
     if (dtype == 0)
-        hipLaunchKernelGGL((simple_kernel<float, double>), grid, block, lds, stream, a);
+        return launch_kernel((simple_kernel<float, double>), grid, block, lds, stream, a);
     else
-        hipLaunchKernelGGL((simple_kernel<unsigned short, float>), grid, block, lds, stream, a);
-    return hipGetLastError();
+        return launch_kernel((simple_kernel<unsigned short, float>), grid, block, lds, stream, a);
 }
 
 } // namespace pskv

@@ -174,13 +174,18 @@ struct Stager {
 // is the same for the whole wavefront).  Written as an instruction rather than through the
 // compiler's builtin: the compiler would make every later LDS read wait for all such requests
 // still in flight.  Its own bookkeeping of the vector memory counter stays on the safe side:
-// requests it does not know of can only make its waits longer.  M0 carries the LDS address;
-// nothing else in this kernel uses M0.
+// requests it does not know of can only make its waits longer.  M0 carries the LDS address and
+// is declared clobbered: the statement then counts as a write of M0 for the compiler's passes
+// that merge and hoist its own M0 set-ups, which keeps them from moving one across it.  (M0 is a
+// reserved register, never allocated, which is all the warning silenced here has to say.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ inline void request_to_lds(const unsigned char *g, lds_u8 *lds_base)
 {
     const unsigned lds_addr = (unsigned)(unsigned long long)lds_base;
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 // s_waitcnt immediate (gfx9 encoding): vector memory counter at most n (n < 16), the others untouched
 #define PSKV_WAIT_VM(n) __builtin_amdgcn_s_waitcnt(0x0F70 | (n))
 
@@ -735,7 +740,7 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
 
 int device_cu_count(hipError_t &e)
 {
-    static int cu_by_device[kMaxDevices] = {};
+    static DeviceSlots cu_by_device;
     return device_setup_once(cu_by_device, e, [] {
         hipError_t s = hipFuncSetAttribute(reinterpret_cast<const void *>(stream_general_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
@@ -801,17 +806,15 @@ hipError_t launch_stream(const Args &a, hipStream_t stream)
         const long long cpasses = (units + 7) / 8 * 8 * cs.ngrp;
         if (nblk_c * 10 >= (long long)cs.ngrp * kNW * 6 && cpasses <= 0x7fffffffLL - 8) {
             const unsigned cgrid = (unsigned)(cpasses < num_cu ? cpasses : num_cu);
-            hipLaunchKernelGGL(stream_candidate_kernel, dim3(cgrid), dim3(kNW * 64), kLdsBytes, stream, a, (int)cpasses, cs);
-            return hipGetLastError();
+            return launch_kernel(stream_candidate_kernel, dim3(cgrid), dim3(kNW * 64), kLdsBytes, stream, a, (int)cpasses, cs);
         }
     }
     if (!pipelined)
-        hipLaunchKernelGGL(stream_general_kernel, dim3(grid), dim3(kNW * 64), kLdsBytes, stream, a, (int)npasses);
+        return launch_kernel(stream_general_kernel, dim3(grid), dim3(kNW * 64), kLdsBytes, stream, a, (int)npasses);
     else if (a.S <= kTileKeys)
-        hipLaunchKernelGGL(stream_pipelined_kernel<true>, dim3(grid), dim3(kNW * 64), kLdsBytes, stream, a, (int)npasses);
+        return launch_kernel(stream_pipelined_kernel<true>, dim3(grid), dim3(kNW * 64), kLdsBytes, stream, a, (int)npasses);
     else
-        hipLaunchKernelGGL(stream_pipelined_kernel<false>, dim3(grid), dim3(kNW * 64), kLdsBytes, stream, a, (int)npasses);
-    return hipGetLastError();
+        return launch_kernel(stream_pipelined_kernel<false>, dim3(grid), dim3(kNW * 64), kLdsBytes, stream, a, (int)npasses);
 }
 
 } // namespace pskv

@@ -100,10 +100,17 @@ def test_fwd_refuses_null_and_misaligned_pointers_before_any_launch():
     assert rc == pk.PSKV_ERR_INVALID_ARG and "aligned" in pk.pskv_last_error()
     rc = lib.pskv_attn_fwd(ctypes.byref(p), a, a, a, a, a, None, a, None, None, 0, None)
     assert rc == pk.PSKV_ERR_INVALID_ARG and "alias" in pk.pskv_last_error()
-    ms = ctypes.c_float()
-    rc = lib.pskv_attn_fwd_timed(ctypes.byref(p), a, a, a, a, a, None, ctypes.c_void_p(0x2000), None,
-                                 None, 0, None, 0, ctypes.byref(ms))
-    assert rc == pk.PSKV_ERR_INVALID_ARG
+    # overlap is judged on address ranges, not on first bytes: out starting inside q, q starting inside out
+    big = 1 << 40
+    q_bytes = p.B * p.S * p.Hq * p.D * 4
+    for q_at, out_at in ((big, big + 256), (big + q_bytes - 16, big)):
+        rc = lib.pskv_attn_fwd(ctypes.byref(p), ctypes.c_void_p(q_at), a, a, a, a, None, ctypes.c_void_p(out_at), None,
+                               None, 0, None)
+        assert rc == pk.PSKV_ERR_INVALID_ARG and "out overlaps q" in pk.pskv_last_error()
+    # lse inside an input
+    rc = lib.pskv_attn_fwd(ctypes.byref(p), ctypes.c_void_p(big), a, a, a, a, None, ctypes.c_void_p(2 * big),
+                           ctypes.c_void_p(big + 64), None, 0, None)
+    assert rc == pk.PSKV_ERR_INVALID_ARG and "lse overlaps q" in pk.pskv_last_error()
 
 
 def test_bwd_refuses_bad_pointers_before_any_launch():
@@ -135,6 +142,47 @@ def test_bwd_refuses_bad_pointers_before_any_launch():
     assert rc == pk.PSKV_ERR_INVALID_ARG and "reserved" in pk.pskv_last_error()
     rc = lib.pskv_attn_bwd_multi(None, a, a, a, a, a, None, None, out, lse, dout, b, c, d_, None, 0, None)
     assert rc == pk.PSKV_ERR_INVALID_ARG
+
+
+def test_bwd_refuses_a_workspace_inside_a_tensor_and_gradient_slices_that_run_into_each_other():
+    lib = pk.load()
+    p = ok(dtype="bf16", D=128)
+    g = 1 << 36
+    q, ks, vs, kp, vp, out, lse, dout, dq, dk, dv = (ctypes.c_void_p(g * i) for i in range(1, 12))
+    need = lib.pskv_attn_bwd_workspace_bytes(ctypes.byref(p))
+    rc = lib.pskv_attn_bwd(ctypes.byref(p), q, ks, vs, kp, vp, None, out, lse, dout, dq, dk, dv,
+                           ctypes.c_void_p(g * 11 + 4096), need, None)       # inside dv
+    assert rc == pk.PSKV_ERR_WORKSPACE and "workspace overlaps dv_suf" in pk.pskv_last_error()
+    rc = lib.pskv_attn_bwd(ctypes.byref(p), q, ks, vs, kp, vp, None, out, lse, dout, dq, dk, dv,
+                           ctypes.c_void_p(g * 12 + 8), need, None)
+    assert rc == pk.PSKV_ERR_WORKSPACE and "aligned" in pk.pskv_last_error()
+    # column slices of one fused [B,S,(Hq+2Hkv),D] gradient buffer interleave without sharing a byte and are
+    # accepted (GPU tests run them); slices whose per-token spans run into each other are not
+    fused = ok(dtype="bf16", D=128, Hq=4, Hkv=2, q_stride_s=8 * 128, q_stride_b=16 * 8 * 128,
+               ks_stride_s=8 * 128, ks_stride_b=16 * 8 * 128)
+    base = 13 * g
+    dq_f, dk_f, dv_f = (ctypes.c_void_p(base + off * 128 * 2) for off in (0, 3, 6))   # dk starts inside dq's 4 heads
+    rc = lib.pskv_attn_bwd(ctypes.byref(fused), q, ks, vs, kp, vp, None, out, lse, dout, dq_f, dk_f, dv_f, None, 0, None)
+    assert rc == pk.PSKV_ERR_INVALID_ARG and "dq overlaps dk_suf" in pk.pskv_last_error()
+
+
+def test_binding_refuses_expanded_views():
+    """The ABI reads stride 0 as "contiguous": a broadcast view must be refused, not read as dense."""
+    import torch
+    q = torch.zeros(4, 8, 4, 128, dtype=torch.bfloat16)
+    ks = torch.zeros(4, 8, 2, 128, dtype=torch.bfloat16)
+    kp = torch.zeros(16, 2, 128, dtype=torch.bfloat16)
+    pk._params_from_tensors(q, ks, kp, q.clone(), "auto", 0.0)              # dense tensors are fine
+    with pytest.raises(ValueError, match="stride 0"):
+        pk._params_from_tensors(q[:1].expand(4, 8, 4, 128), ks, kp, q.clone(), "auto", 0.0)
+    with pytest.raises(ValueError, match="stride 0"):
+        pk._params_from_tensors(q, ks[:1].expand(4, 8, 2, 128), kp, q.clone(), "auto", 0.0)
+    with pytest.raises(ValueError, match="stride 0"):                       # one prefix broadcast over the instructions
+        kpm = kp[None].expand(2, 16, 2, 128)
+        pk.make_multi_params(pk._params_from_tensors(q, ks, kpm[0], q.clone(), "auto", 0.0), 2, pk._stride(kpm, 0, "k_pre"))
+    # a dimension of size 1 has no stride to speak of: whatever torch reports for it is not passed on
+    one = pk._params_from_tensors(q[:1], ks[:1], kp, q[:1].clone(), "auto", 0.0)
+    assert one.q_stride_b == 0 and one.B == 1
 
 
 def test_bwd_workspace_size():

@@ -31,6 +31,21 @@ def test_inline_assembly_is_constraints_only_or_the_lds_request():
             assert ok, f"{p.name}: inline instruction(s) {t!r}: use a compiler intrinsic instead"
 
 
+def test_an_asm_statement_that_writes_m0_says_so_in_its_clobber_list():
+    """The compiler may keep a value of its own in M0 across an asm statement unless told otherwise."""
+    for p in SOURCES:
+        text = p.read_text()
+        for m in re.finditer(r"\basm\s*(?:volatile\s*)?\(", text):
+            depth, i = 1, m.end()
+            while depth and i < len(text):      # the whole statement, up to its closing parenthesis
+                depth += {"(": 1, ")": -1}.get(text[i], 0)
+                i += 1
+            stmt = text[m.start():i]
+            if re.search(r"\bm0\s*,", "".join(re.findall(r"\"((?:[^\"\\]|\\.)*)\"", stmt.split(":")[0]))):
+                clobbers = stmt.rsplit(":", 1)[1]
+                assert '"m0"' in clobbers, f"{p.name}: asm statement writes m0 without declaring the clobber"
+
+
 def test_no_packed_fp32_by_hand_and_the_flag_is_set():
     for p in SOURCES:
         text = p.read_text()
