@@ -18,7 +18,7 @@
  * All pointers except the params struct and the returned strings are DEVICE pointers owned
  * by the caller.  The library allocates, frees and retains no device memory and keeps no
  * state between calls apart from a one-time set-up per device (compute-unit count, LDS limits
- * of its kernels), done at the first call on that device and
+ * of its kernels, address of its built-in scratch), done at the first call on that device and
  * safe against host threads that make that first call at the same time.  The stream must belong
  * to the device that is current when the call is made.  Work is enqueued on the given stream and
  * the call returns without synchronising (no entry point synchronises, creates events or waits);
@@ -47,7 +47,8 @@ typedef enum {
     PSKV_OK = 0,
     PSKV_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, Hq % Hkv != 0, misaligned pointer/stride */
     PSKV_ERR_UNSUPPORTED = 2, /* shape or dtype outside what the kernels cover */
-    PSKV_ERR_WORKSPACE = 3,   /* a workspace that cannot be used (misaligned, overlapping a tensor) */
+    PSKV_ERR_WORKSPACE = 3,   /* a workspace that cannot be used (misaligned, overlapping a tensor), or a
+                                 problem that needs more scratch than pskv_attn_bwd_noalloc has built in */
     PSKV_ERR_HIP = 4          /* the HIP runtime refused a launch or query */
 } pskv_status;
 
@@ -243,6 +244,30 @@ pskv_status pskv_attn_bwd_multi(const pskv_multi_params *p,
                                 void *dq, void *dk_suf, void *dv_suf,
                                 void *workspace, size_t workspace_bytes,
                                 void *hip_stream);
+
+/*
+ * pskv_attn_bwd for callers that cannot allocate device memory and have no workspace to bring: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and
+ * results as pskv_attn_bwd without the workspace pair: the B*Hq*S floats that the first kernel hands
+ * to the second live in a fixed array of PSKV_NOALLOC_SCRATCH_BYTES that is part of the library's
+ * code object (every GPU the library runs on holds one copy until the process ends).  The call
+ * allocates and frees nothing, on the device or through any library.  A problem with
+ * B*Hq*S*4 > PSKV_NOALLOC_SCRATCH_BYTES is refused with PSKV_ERR_WORKSPACE (nothing launched); shapes
+ * whose kernels use no scratch (fp32 tensors, D != 128) are served whatever their size.
+ * All calls on one GPU share that array: two such calls that may run at the same time on one GPU
+ * (different streams, or different host threads) race on it and must be ordered by the caller.
+ * Nothing in it has to start from zero: the first kernel writes every entry the second reads.
+ * The first call on a device looks up the array's address (one-time set-up): make it outside any
+ * graph capture.
+ */
+#define PSKV_NOALLOC_SCRATCH_BYTES (8u << 20)
+pskv_status pskv_attn_bwd_noalloc(const pskv_attn_params *p,
+                                  const void *q, const void *k_suf, const void *v_suf,
+                                  const void *k_pre, const void *v_pre,
+                                  const int32_t *suf_len,
+                                  const void *out, const float *lse, const void *dout,
+                                  void *dq, void *dk_suf, void *dv_suf,
+                                  void *hip_stream);
 
 #ifdef __cplusplus
 }

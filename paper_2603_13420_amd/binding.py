@@ -20,7 +20,8 @@ _IMPL = {"auto": PSKV_IMPL_AUTO, "simple": PSKV_IMPL_SIMPLE, "mfma": PSKV_IMPL_M
 EXPORTS = ["pskv_version", "pskv_status_str", "pskv_last_error", "pskv_attn_fwd_workspace_bytes",
            "pskv_attn_validate", "pskv_attn_fwd",
            "pskv_attn_multi_validate", "pskv_attn_fwd_multi", "pskv_attn_bwd", "pskv_attn_bwd_multi",
-           "pskv_attn_bwd_workspace_bytes"]
+           "pskv_attn_bwd_workspace_bytes", "pskv_attn_bwd_noalloc"]
+PSKV_NOALLOC_SCRATCH_BYTES = 8 << 20
 
 
 class pskv_attn_params(ctypes.Structure):
@@ -80,6 +81,8 @@ def load():
     lib.pskv_attn_bwd_workspace_bytes.argtypes = [P]
     lib.pskv_attn_bwd_multi.restype = ctypes.c_int
     lib.pskv_attn_bwd_multi.argtypes = [PM] + [vp] * 14 + [ctypes.c_size_t, vp]
+    lib.pskv_attn_bwd_noalloc.restype = ctypes.c_int
+    lib.pskv_attn_bwd_noalloc.argtypes = [P] + [vp] * 13
     _lib = lib
     return lib
 
@@ -379,3 +382,30 @@ def pskv_attn_bwd_multi(q, k_suf, v_suf, k_pre, v_pre, pre_len, suf_len, out, ls
         _raise(rc)
     return dq, dk_suf, dv_suf
 
+
+def pskv_attn_bwd_noalloc(q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse, dout, dq, dk_suf, dv_suf,
+                          impl: str = "auto", scale: float = 0.0, stream: Optional[int] = None):
+    """pskv_attn_bwd through the entry point that allocates nothing: the gradient tensors are the
+    caller's, the scratch is the library's built-in array (refused with PSKV_ERR_WORKSPACE when
+    B*Hq*S*4 exceeds PSKV_NOALLOC_SCRATCH_BYTES), and this wrapper creates no tensor either."""
+    import torch
+    if lse is None:
+        raise ValueError("the backward pass needs the forward pass's lse")
+    _check_inputs(q, k_suf, v_suf, k_pre, v_pre, suf_len, out, lse)
+    if tuple(dout.shape) != tuple(out.shape) or dout.stride() != out.stride() or dout.dtype != q.dtype:
+        raise ValueError("dout must have the shape, strides and dtype of out")
+    if dq.shape != q.shape or dq.stride() != q.stride() or dq.dtype != q.dtype:
+        raise ValueError("dq must have the shape, strides and dtype of q")
+    for name, t in (("dk_suf", dk_suf), ("dv_suf", dv_suf)):
+        if t.shape != k_suf.shape or t.stride() != k_suf.stride() or t.dtype != q.dtype:
+            raise ValueError(f"{name} must have the shape, strides and dtype of k_suf")
+    p = _params_from_tensors(q, k_suf, k_pre, out, impl, scale)
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device).cuda_stream
+    with torch.cuda.device(q.device):
+        rc = load().pskv_attn_bwd_noalloc(ctypes.byref(p), _ptr(q), _ptr(k_suf), _ptr(v_suf), _ptr(k_pre), _ptr(v_pre),
+                                          _ptr(suf_len), _ptr(out), _ptr(lse), _ptr(dout), _ptr(dq), _ptr(dk_suf),
+                                          _ptr(dv_suf), ctypes.c_void_p(stream))
+    if rc != PSKV_OK:
+        _raise(rc)
+    return dq, dk_suf, dv_suf

@@ -405,4 +405,32 @@ pskv_status pskv_attn_bwd_multi(const pskv_multi_params *p, const void *q, const
                       dk_suf, dv_suf, workspace, workspace_bytes, hip_stream);
 }
 
+pskv_status pskv_attn_bwd_noalloc(const pskv_attn_params *p, const void *q, const void *k_suf, const void *v_suf,
+                                  const void *k_pre, const void *v_pre, const int32_t *suf_len, const void *out,
+                                  const float *lse, const void *dout, void *dq, void *dk_suf, void *dv_suf,
+                                  void *hip_stream)
+{
+    pskv::Args a{};
+    bool use_mfma = false;
+    pskv_status s = resolve(p, 1, 0, a, use_mfma);
+    if (s != PSKV_OK)
+        return s;
+    void *scratch_ptr = nullptr;
+    size_t scratch_bytes = 0;
+    if (use_mfma && pskv::bwd_mfma_supported(a, p->dtype)) { // the kernels that use the scratch
+        const size_t need = (size_t)p->B * (size_t)p->Hq * (size_t)p->S * sizeof(float);
+        if (need > pskv::kNoAllocScratchBytes)
+            return fail(PSKV_ERR_WORKSPACE,
+                        "B*Hq*S*4 = %zu bytes of scratch exceed the %zu bytes built into the library: use pskv_attn_bwd "
+                        "with a workspace of the caller's",
+                        need, (size_t)pskv::kNoAllocScratchBytes);
+        const hipError_t e = pskv::noalloc_scratch(&scratch_ptr);
+        if (e != hipSuccess)
+            return fail(PSKV_ERR_HIP, "address of the built-in scratch: %s", hipGetErrorString(e));
+        scratch_bytes = need;
+    }
+    return launch_bwd(p, 1, 0, q, k_suf, v_suf, k_pre, v_pre, nullptr, suf_len, out, lse, dout, dq, dk_suf, dv_suf,
+                      scratch_ptr, scratch_bytes, hip_stream);
+}
+
 } // extern "C"

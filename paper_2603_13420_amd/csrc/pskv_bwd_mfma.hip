@@ -21,6 +21,12 @@
 // A second kernel further down keeps short prefixes resident in LDS instead of streaming them.
 #include "pskv_mfma.hpp"
 
+// Scratch of the entry point that allocates nothing (pskv_attn_bwd_noalloc): <dout_row, out_row> of
+// every query row, B*Hq*S floats, handed from the dq kernel to the dk/dv kernel.  In host code this
+// name is a stand-in for the symbol, not a device address: the address comes from
+// hipGetSymbolAddress (noalloc_scratch() at the end of this file) and is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[pskv::kNoAllocScratchBytes];
+
 namespace pskv {
 namespace {
 
@@ -760,6 +766,30 @@ hipError_t launch_bwd_dkv_mfma(const BwdArgs &g, hipStream_t stream)
     else
         return launch_kernel(bwd_dkv_mfma_kernel<false>, dim3(grid), dim3(kDkvWaves * 64), kDkvLdsBytes, stream, g, (int)nunits,
                            nkt);
+}
+
+hipError_t noalloc_scratch(void **ptr)
+{
+    static std::mutex mu;
+    static void *by_device[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return e;
+    if (dev < 0 || dev >= kMaxDevices)
+        return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> guard(mu);
+    if (!by_device[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess)
+            return e;
+        if (!p)
+            return hipErrorInvalidSymbol;
+        by_device[dev] = p;
+    }
+    *ptr = by_device[dev];
+    return hipSuccess;
 }
 
 hipError_t launch_bwd_dq_mfma(const BwdArgs &g, hipStream_t stream)

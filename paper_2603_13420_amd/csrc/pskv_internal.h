@@ -74,6 +74,11 @@ hipError_t launch_bwd_dkv_simple(const BwdArgs &g, int dtype, hipStream_t stream
 // Matrix-core kernels for dq and for dk/dv: bf16, D == 128 (prefixes of up to 256 rows stay resident
 // in LDS for dq, longer ones are streamed).
 bool bwd_mfma_supported(const Args &a, int dtype);
+// Scratch for callers that cannot allocate: a fixed array in device memory that is part of the
+// library's code object.  noalloc_scratch() hands out its address on the current device (looked
+// up once per device: every device holds its own copy at its own address).
+constexpr size_t kNoAllocScratchBytes = 8u << 20;
+hipError_t noalloc_scratch(void **ptr);
 hipError_t launch_bwd_dq_mfma(const BwdArgs &g, hipStream_t stream);
 hipError_t launch_bwd_dkv_mfma(const BwdArgs &g, hipStream_t stream);
 

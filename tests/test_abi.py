@@ -144,7 +144,7 @@ def test_bwd_refuses_bad_pointers_before_any_launch():
     assert rc == pk.PSKV_ERR_INVALID_ARG
 
 
-def test_bwd_refuses_a_workspace_inside_a_tensor_and_gradient_slices_that_run_into_each_other():
+def test_bwd_refuses_a_workspace_inside_a_tensor_and_noalloc_refuses_what_its_scratch_cannot_hold():
     lib = pk.load()
     p = ok(dtype="bf16", D=128)
     g = 1 << 36
@@ -164,6 +164,15 @@ def test_bwd_refuses_a_workspace_inside_a_tensor_and_gradient_slices_that_run_in
     dq_f, dk_f, dv_f = (ctypes.c_void_p(base + off * 128 * 2) for off in (0, 3, 6))   # dk starts inside dq's 4 heads
     rc = lib.pskv_attn_bwd(ctypes.byref(fused), q, ks, vs, kp, vp, None, out, lse, dout, dq_f, dk_f, dv_f, None, 0, None)
     assert rc == pk.PSKV_ERR_INVALID_ARG and "dq overlaps dk_suf" in pk.pskv_last_error()
+    # the entry point that allocates nothing: B*Hq*S*4 beyond its built-in scratch is refused on the host
+    huge = ok(B=4096, S=64, P=512, Hq=40, Hkv=40, D=128, dtype="bf16")
+    assert 4096 * 40 * 64 * 4 > pk.PSKV_NOALLOC_SCRATCH_BYTES
+    rc = lib.pskv_attn_bwd_noalloc(ctypes.byref(huge), q, ks, vs, kp, vp, None, out, lse, dout, dq, dk, dv, None)
+    assert rc == pk.PSKV_ERR_WORKSPACE and "exceed" in pk.pskv_last_error()
+    rc = lib.pskv_attn_bwd_noalloc(None, q, ks, vs, kp, vp, None, out, lse, dout, dq, dk, dv, None)
+    assert rc == pk.PSKV_ERR_INVALID_ARG
+    header = open(os.path.join(ROOT, "include", "pskv.h")).read()
+    assert "#define PSKV_NOALLOC_SCRATCH_BYTES (8u << 20)" in header
 
 
 def test_binding_refuses_expanded_views():
