@@ -17,8 +17,12 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x",
          "-Wno-unused-command-line-argument", "-Wall", "-ffp-contract=fast"]
 
 
-def build_library(verbose: bool = False, extra=()) -> str:
-    cmd = [HIPCC, *FLAGS, *extra, "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+# bench.py's measurement helper (an MFMA-only kernel): a library of its own, outside the attention ABI
+PROBE_LIB = os.path.join(HERE, "libpskv_probe.so")
+PROBE_SOURCES = ["bench_probe.hip"]
+
+
+def _compile(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -28,6 +32,11 @@ def build_library(verbose: bool = False, extra=()) -> str:
         raise RuntimeError("hipcc failed:\n" + res.stdout)
     if verbose and out.strip():
         print(out)
+
+
+def build_library(verbose: bool = False, extra=()) -> str:
+    _compile([HIPCC, *FLAGS, *extra, "-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES], verbose)
+    _compile([HIPCC, *FLAGS, *extra, "-o", PROBE_LIB] + [os.path.join(CSRC, s) for s in PROBE_SOURCES], verbose)
     return LIB
 
 

@@ -283,3 +283,54 @@ def make_multi_inputs(w: MultiWorkload, pad: str = "nan", seed: Optional[int] = 
 
 def custom_multi_workload(name, Np, C, P, pre_lo, pre_hi, S, len_lo, len_hi, Hq, Hkv, D, dtype, index=100):
     return MultiWorkload(name, Np, C, P, pre_lo, pre_hi, S, len_lo, len_hi, Hq, Hkv, D, dtype, index)
+
+
+# ---------------------------------------------------------------------------------------------
+# Host tensors <-> torch tensors on the GPU (data movement only), and the seeded incoming gradient
+# of the backward pass.
+# ---------------------------------------------------------------------------------------------
+def _to_torch(a: np.ndarray, dtype: str, device):
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype == "bf16":
+        t = t.view(torch.bfloat16)
+    return t.to(device)
+
+
+def to_device(inp: Inputs, device="cuda:0") -> dict:
+    """The problem's tensors on the GPU, keyed like the arguments of pskv_attn_fwd (k_pre, v_pre None when P == 0)."""
+    import torch
+    dt = inp.w.dtype
+    return dict(q=_to_torch(inp.q, dt, device), k_suf=_to_torch(inp.k_suf, dt, device), v_suf=_to_torch(inp.v_suf, dt, device),
+                k_pre=_to_torch(inp.k_pre, dt, device) if inp.w.P > 0 else None,
+                v_pre=_to_torch(inp.v_pre, dt, device) if inp.w.P > 0 else None,
+                suf_len=torch.from_numpy(inp.suf_len).to(device))
+
+
+def to_device_multi(inp: MultiInputs, device="cuda:0") -> dict:
+    import torch
+    dt = inp.w.dtype
+    return dict(q=_to_torch(inp.q, dt, device), k_suf=_to_torch(inp.k_suf, dt, device), v_suf=_to_torch(inp.v_suf, dt, device),
+                k_pre=_to_torch(inp.k_pre, dt, device), v_pre=_to_torch(inp.v_pre, dt, device),
+                pre_len=torch.from_numpy(inp.pre_len).to(device), suf_len=torch.from_numpy(inp.suf_len).to(device))
+
+
+def out_to_f64(t) -> np.ndarray:
+    """A result tensor of the GPU as float64 on the host (bf16 widened exactly)."""
+    import torch
+    if t.dtype == torch.bfloat16:
+        return bf16_bits_to_f32(t.view(torch.uint16).cpu().numpy()).astype(np.float64)
+    return t.cpu().numpy().astype(np.float64)
+
+
+def make_dout(inp, seed: int):
+    """Seeded N(0,1) incoming gradient of the backward pass in the workload's storage type, NaN on
+    padded rows.  Returns (host array in storage form, the same values as float64)."""
+    w = inp.w
+    rng = np.random.default_rng(seed)
+    a = rng.standard_normal(size=(w.B, w.S, w.Hq, w.D), dtype=np.float32)
+    a[np.arange(w.S)[None, :] >= inp.suf_len[:, None]] = np.nan
+    if w.dtype == "bf16":
+        bits = f32_to_bf16_bits(a)
+        return bits, bf16_bits_to_f32(bits).astype(np.float64)
+    return a, a.astype(np.float64)
