@@ -91,8 +91,9 @@ typedef struct {
 /* Library version as major*10000 + minor*100 + patch. Never fails. */
 int pskv_version(void);
 
-/* Static English name of a status code. Never NULL. */
-const char *pskv_status_str(pskv_status s);
+/* Static English name of a status code; "unknown status" for any other number. Never NULL.  (Takes an
+ * int so that a number outside the enumeration is a defined argument in C++ callers as well.) */
+const char *pskv_status_str(int status);
 
 /* Detail text of the last error raised on the calling thread ("" if none). The pointer is
  * valid until the next library call on the same thread. */

@@ -219,9 +219,9 @@ extern "C" {
 
 int pskv_version(void) { return 100; }
 
-const char *pskv_status_str(pskv_status s)
+const char *pskv_status_str(int status)
 {
-    switch (s) {
+    switch (status) {
     case PSKV_OK: return "ok";
     case PSKV_ERR_INVALID_ARG: return "invalid argument";
     case PSKV_ERR_UNSUPPORTED: return "unsupported shape or dtype";
