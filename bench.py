@@ -78,15 +78,15 @@ def alg_counts(w, suf_len, pre_len=None):
 # kernel sources they were taken on (kernel_source_rev()).  When the sources have changed since, the
 # bench line reports no traffic and says why, instead of a figure that no longer holds.
 HBM_TRAFFIC = {
-    "gqa8b_bf16": {"file": "resident_pipelined_kernel_gqa8b_bf16_hbm_traffic.txt", "rev": "unset", "mfma_flops": None, "fetch_kib": 143007.0, "fetch_scale": 2.0, "write_kib": 197636.0, "write_scale": 1.0},
-    "ldec_gqa8b_bf16": {"file": "stream_candidate_kernel_ldec_gqa8b_bf16_hbm_traffic.txt", "rev": "unset", "mfma_flops": None, "fetch_kib": 237993.6, "fetch_scale": 2.0, "write_kib": 327680.1, "write_scale": 1.0},
-    "longprefix_bf16": {"file": "stream_pipelined_kernel_longprefix_bf16_hbm_traffic.txt", "rev": "unset", "mfma_flops": None, "fetch_kib": 63003.5, "fetch_scale": 2.0, "write_kib": 66566.3, "write_scale": 1.0},
-    "multi8_gqa8b_bf16": {"file": "resident_pipelined_kernel_multi8_gqa8b_bf16_hbm_traffic.txt", "rev": "unset", "mfma_flops": None, "fetch_kib": 142711.0, "fetch_scale": 2.0, "write_kib": 197632.0, "write_scale": 1.0},
-    "mha13b_bf16": {"file": "stream_pipelined_kernel_mha13b_bf16_hbm_traffic.txt", "rev": "unset", "mfma_flops": None, "fetch_kib": 3919561.6, "fetch_scale": 2.0, "write_kib": 2622464.0, "write_scale": 1.0},
-    "multi32_gqa8b_bf16": {"file": "resident_pipelined_kernel_multi32_gqa8b_bf16_hbm_traffic.txt", "rev": "unset", "mfma_flops": None, "fetch_kib": 151957.0, "fetch_scale": 2.0, "write_kib": 197632.0, "write_scale": 1.0},
-    "multi4_long_bf16": {"file": "stream_pipelined_kernel_multi4_long_bf16_hbm_traffic.txt", "rev": "unset", "mfma_flops": None, "fetch_kib": 60091.5, "fetch_scale": 2.0, "write_kib": 66560.0, "write_scale": 1.0},
-    "ldec_qwen7b_bf16": {"file": "stream_candidate_kernel_ldec_qwen7b_bf16_hbm_traffic.txt", "rev": "unset", "mfma_flops": None, "fetch_kib": 180835.4, "fetch_scale": 2.0, "write_kib": 286720.0, "write_scale": 1.0},
-    "mha7b_bf16": {"file": "resident_general_kernel_mha7b_bf16_hbm_traffic.txt", "rev": "unset", "mfma_flops": None, "fetch_kib": 129055.0, "fetch_scale": 2.0, "write_kib": 81921.7, "write_scale": 1.0},
+    "gqa8b_bf16": {"file": "resident_pipelined_kernel_gqa8b_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 111887253504.0, "fetch_kib": 142208.0, "fetch_scale": 2.0, "write_kib": 197632.8, "write_scale": 1.0},
+    "ldec_gqa8b_bf16": {"file": "stream_candidate_kernel_ldec_gqa8b_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 134809124864.0, "fetch_kib": 238004.4, "fetch_scale": 2.0, "write_kib": 327680.2, "write_scale": 1.0},
+    "ldec_qwen7b_bf16": {"file": "stream_candidate_kernel_ldec_qwen7b_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 116735868928.0, "fetch_kib": 180886.7, "fetch_scale": 2.0, "write_kib": 286720.0, "write_scale": 1.0},
+    "longprefix_bf16": {"file": "stream_pipelined_kernel_longprefix_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 279172874240.0, "fetch_kib": 62930.4, "fetch_scale": 2.0, "write_kib": 66569.8, "write_scale": 1.0},
+    "mha13b_bf16": {"file": "stream_pipelined_kernel_mha13b_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 3004086353920.0, "fetch_kib": 3937667.2, "fetch_scale": 2.0, "write_kib": 2622464.0, "write_scale": 1.0},
+    "mha7b_bf16": {"file": "resident_general_kernel_mha7b_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 34359738368.0, "fetch_kib": 129183.0, "fetch_scale": 2.0, "write_kib": 81920.8, "write_scale": 1.0},
+    "multi32_gqa8b_bf16": {"file": "resident_pipelined_kernel_multi32_gqa8b_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 85198897152.0, "fetch_kib": 151814.5, "fetch_scale": 2.0, "write_kib": 197632.0, "write_scale": 1.0},
+    "multi4_long_bf16": {"file": "stream_pipelined_kernel_multi4_long_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 73014444032.0, "fetch_kib": 60179.9, "fetch_scale": 2.0, "write_kib": 66560.0, "write_scale": 1.0},
+    "multi8_gqa8b_bf16": {"file": "resident_pipelined_kernel_multi8_gqa8b_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 93021274112.0, "fetch_kib": 142292.6, "fetch_scale": 2.0, "write_kib": 197632.0, "write_scale": 1.0},
 }
 
 
@@ -134,7 +134,7 @@ def cpu_baseline_multi(inp, budget_s=12.0):
 
 # The same for one backward call (its two kernels together).
 HBM_TRAFFIC_BWD = {
-    "gqa8b_bf16": {"file": "bwd_kernels_gqa8b_bf16_hbm_traffic.txt", "rev": "unset", "fetch_kib": 302485.0 + 208528.0, "fetch_scale": 2.0, "write_kib": 199247.7 + 98304.0, "write_scale": 1.0},
+    "gqa8b_bf16": {"file": "bwd_kernels_gqa8b_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 205126631424.0, "fetch_kib": 510963.4, "fetch_scale": 2.0, "write_kib": 297560.5, "write_scale": 1.0},
 }
 
 
@@ -176,7 +176,7 @@ def bench_backward(args):
                          workspace=d["ws"])
 
     steps, warmup = min(args.steps, 400), min(args.warmup, 100)
-    for i in range(PRERAMP_LAUNCHES // 2 + warmup):      # clock ramp (untimed, fixed), then the counted warm-up
+    for i in range(args.preramp // 2 + warmup):      # clock ramp (untimed, fixed), then the counted warm-up
         call(i % nsets)
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -208,7 +208,7 @@ def bench_backward(args):
     roof["traffic_unit"] = "bytes per step"
     roof["kernel_ms"] = kern_ms
     line = {"metric": "candidate suffixes/sec per attention layer, backward pass", "value": w.B / (ms_per_step * 1e-3),
-            "unit": "candidates/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "preramp_launches": PRERAMP_LAUNCHES // 2,
+            "unit": "candidates/s", "n_gpus": 1, "steps": steps, "warmup": warmup, "preramp_launches": args.preramp // 2,
             "ms_per_step": ms_per_step,
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
             "dtype": "bf16" if mfma else ("f64" if w.dtype == "f32" else "f32"), "data": "synthetic",
@@ -247,7 +247,7 @@ def measure_mfma_peak(torch, stream) -> float:
     lib.pskv_probe_mfma_launch.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.POINTER(ctypes.c_double)]
     sink = torch.zeros(1, dtype=torch.float32, device="cuda:0")
     flops = ctypes.c_double(0.0)
-    iters = 4000        # about 0.1 ms per launch
+    iters = 500         # 0.2 ms per launch
 
     def launch():
         rc = lib.pskv_probe_mfma_launch(iters, ctypes.c_void_p(sink.data_ptr()), ctypes.c_void_p(stream), ctypes.byref(flops))
@@ -279,6 +279,9 @@ def main():
                          "standard_kv = prefix K/V physically repeated per candidate and kept resident (Eq. 3); "
                          "lazy_expand = the compact prefix expanded into a per-layer workspace inside every step "
                          "(App. F.5/F.6)")
+    ap.add_argument("--preramp", type=int, default=PRERAMP_LAUNCHES,
+                    help="untimed launches before the counted warm-up that let the shader clock climb from idle "
+                         "(reported as preramp_launches; counter-collection runs set it to 0)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain element-wise copy of known size (the reference that the "
@@ -416,11 +419,12 @@ def main():
     chk = parity.compare(got, ref, sub.suf_len, w.dtype, "bench self-check")
 
     # what the matrix cores sustain on this machine with nothing else going on
-    mfma_measured = measure_mfma_peak(torch, stream) if w.dtype == "bf16" and args.impl != "simple" else None
+    mfma_measured = (measure_mfma_peak(torch, stream)
+                     if w.dtype == "bf16" and args.impl != "simple" and args.preramp > 0 else None)
 
     # launches timed one at a time, each between its own pair of events (for comparison only)
     isolated_ms = None
-    if prepared is not None and not multi_call:
+    if prepared is not None and not multi_call and args.preramp > 0:
         per_set = []
         for _ in range(max(1, min(20, args.steps // nsets))):
             for i in range(nsets):
@@ -433,7 +437,7 @@ def main():
         isolated_ms = float(np.mean(per_set))
 
     # ---- clock ramp (untimed, fixed), counted warm-up, timed region ----
-    for i in range(PRERAMP_LAUNCHES):
+    for i in range(args.preramp):
         call(i % nsets)
     for i in range(args.warmup):
         call(i % nsets)
@@ -497,7 +501,7 @@ def main():
 
     line = {
         "metric": "candidate suffixes/sec per attention layer", "value": cand_per_s, "unit": "candidates/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "preramp_launches": PRERAMP_LAUNCHES,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "preramp_launches": args.preramp,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == "bf16" and args.impl != "simple" else ("f64" if w.dtype == "f32" else "f32"),

@@ -10,7 +10,8 @@ import os
 from typing import Optional
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libpskv.so")
+# PSKV_LIB: another build of the library to load instead of the in-tree one (kernel experiments)
+LIB_PATH = os.environ.get("PSKV_LIB") or os.path.join(HERE, "libpskv.so")
 
 PSKV_OK, PSKV_ERR_INVALID_ARG, PSKV_ERR_UNSUPPORTED, PSKV_ERR_WORKSPACE, PSKV_ERR_HIP = range(5)
 PSKV_DTYPE_F32, PSKV_DTYPE_BF16 = 0, 1
