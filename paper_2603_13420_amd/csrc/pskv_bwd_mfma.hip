@@ -60,6 +60,28 @@ __device__ inline long long delta_index(const Args &a, long long b, int rh, int 
 __device__ inline float bf16_lo(unsigned w) { return __uint_as_float(w << 16); }
 __device__ inline float bf16_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
 
+// <dout_row, out_row> of the lane's row from the row's fragments (lane half h holds columns
+// 16*ks + 8*h ..+7 of fragment ks).  Columns 0..63 and 64..127 are summed separately, each across the
+// two lane halves, and then added: the order in which the dk/dv kernel, whose wavefronts hold one
+// half of the columns each, forms the same number when no workspace hands it over - the two agree
+// to the bit.
+__device__ inline float half_dot(const uintx4 (&x)[8], const uintx4 (&y)[8], int half)
+{
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            acc = __builtin_fmaf(bf16_lo(x[4 * half + i][e]), bf16_lo(y[4 * half + i][e]), acc);
+            acc = __builtin_fmaf(bf16_hi(x[4 * half + i][e]), bf16_hi(y[4 * half + i][e]), acc);
+        }
+    return acc + __shfl_xor(acc, 32, 64);
+}
+__device__ inline float dout_dot_out(const uintx4 (&dof)[8], const uintx4 (&of)[8])
+{
+    return half_dot(dof, of, 0) + half_dot(dof, of, 1);
+}
+
 // dS^T of one 32-key tile from its raw scores s and dp; element e is visible iff vis(e).
 // Returns the two B fragments (keys 0..15, 16..31) of the following product.
 template <typename VIS>
@@ -134,18 +156,11 @@ void bwd_dq_mfma_kernel(BwdArgs g, int npasses)
         uintx4 q[8], dof[8];
         load_q(a, X, rld, q);
         load_o_like(a, X, rld, g.dout, dof);
-        float drow = 0.f; // <dout_row, out_row>: this lane's 64 columns, then the other half-wave's
+        float drow; // <dout_row, out_row>
         {
             uintx4 of[8];
             load_o_like(a, X, rld, a.out, of);
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    drow = __builtin_fmaf(bf16_lo(dof[ks][e]), bf16_lo(of[ks][e]), drow);
-                    drow = __builtin_fmaf(bf16_hi(dof[ks][e]), bf16_hi(of[ks][e]), drow);
-                }
-            drow += __shfl_xor(drow, 32, 64);
+            drow = dout_dot_out(dof, of);
         }
         if (g.delta && rvalid && X.h == 0) // kept in the order of the stacked rows: see delta_index
             g.delta[delta_index(a, row.rb, row.rh, row.ri)] = drow;
@@ -377,7 +392,7 @@ void bwd_dq_resident_kernel(BwdArgs g, int per_vh, int vh_slots, int max_tiles)
             const float lse2 = a.lse[((long long)row.b * a.Hq + row.rh) * a.S + row.ri] * kLog2e;
             uintx4 q[8], dof[8];
             load_q_block(a, X, row, q);
-            float drow = 0.f; // <dout_row, out_row>: this lane's 64 columns, then the other half-wave's
+            float drow; // <dout_row, out_row>
             {
                 // rows past the candidate's length take dout and out of its last position, as they do for q
                 const int rld = row.ri < row.len ? row.ri : row.len - 1;
@@ -391,14 +406,7 @@ void bwd_dq_resident_kernel(BwdArgs g, int per_vh, int vh_slots, int max_tiles)
                     dof[ks] = *reinterpret_cast<const uintx4 *>(dorow + 32 * ks);
                     of[ks] = *reinterpret_cast<const uintx4 *>(orow + 32 * ks);
                 }
-#pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        drow = __builtin_fmaf(bf16_lo(dof[ks][e]), bf16_lo(of[ks][e]), drow);
-                        drow = __builtin_fmaf(bf16_hi(dof[ks][e]), bf16_hi(of[ks][e]), drow);
-                    }
-                drow += __shfl_xor(drow, 32, 64);
+                drow = dout_dot_out(dof, of);
             }
             if (g.delta && row.ri < row.len && X.h == 0) // one 128-byte line per block: see delta_index
                 g.delta[delta_index(a, row.b, row.rh, row.ri)] = drow;
@@ -485,22 +493,29 @@ void bwd_dq_resident_kernel(BwdArgs g, int per_vh, int vh_slots, int max_tiles)
 }
 
 // ------------------------------------------------------------------------------------------
-// dk_suf, dv_suf on the matrix cores.  One wavefront per (candidate, KV head, tile of 32 suffix
-// keys, half DH of the 128 output columns: the accumulators of both halves would not fit the
-// register file); it walks over the candidate's 32-row blocks of stacked query rows (i, g) that can see
-// the tile and accumulates, in the non-transposed formulation (a lane owns one key column):
+// dk_suf, dv_suf on the matrix cores.  One workgroup of two wavefronts per (candidate, KV head, tile
+// of 32 suffix keys); wavefront DH owns half DH of the 128 columns (the accumulators of both halves
+// would not fit one register file).  The pair walks over the candidate's 32-row blocks of stacked
+// query rows (i, g) that can see the tile and accumulates, in the non-transposed formulation (a lane
+// owns one key column):
 //     S   = Q K^T          A = Q fragment,   B = K fragment (both straight from global memory)
 //     dP  = dO V^T         A = dO fragment,  B = V fragment
 //     P   = exp2(c S - lse),  dS = P o (dP - D)      per element: row quantities come through LDS
 //     dV^T += dO^T P       A = dO^T through the scratch tile,  B = P packed to bf16
 //     dK^T += Q^T dS       A = Q^T through the scratch tile,   B = dS packed to bf16
+// The first two products contract over the 128 columns: each wavefront forms its own half of that
+// sum from its own half of the columns of q, dout, K and V - the only columns it ever fetches, so
+// that every row of q and dout crosses HBM once per tile and not once per wavefront - and the two
+// halves of S and dP (4 KB each, fp32) change hands through LDS.  The second products need exactly
+// the columns the wavefront already holds.
 // The accumulators of S hold, for lane half h, rows 8*kk + 4*h + t of the block in element
 // 4*kk + t: exactly the order in which the scratch image hands out the rows of dO and Q, so P
 // and dS go from the first products to the second ones through registers only.
 // ------------------------------------------------------------------------------------------
-constexpr int kDkvWaves = 4;
+constexpr int kDkvWaves = 2; // the two column halves of one unit
 constexpr int kDkvAux = 512; // per wavefront: lse, <dout,out> and suffix position of the block's 32 rows
-constexpr int kDkvLdsBytes = kDkvWaves * (kScrBytes + kDkvAux);
+constexpr int kDkvXchBytes = 2 * 16 * 256; // per wavefront: its halves of S and dP, 16 accumulator registers of 256 bytes each
+constexpr int kDkvLdsBytes = kDkvWaves * (kScrBytes + kDkvAux + kDkvXchBytes) + 256; // + the halves of <dout,out>
 
 // O^T-style accumulation of two 32-column groups (dt = 2*DH, 2*DH+1) for one 16-row step whose
 // rows are in registers in scratch-image order: through the scratch tile (cf. pv_from_scratch).
@@ -565,8 +580,7 @@ __device__ inline void pv_half_from_fragments(const Ctx &X, const uintx4 (&frag)
 }
 
 template <int DH, bool HAS_DELTA>
-__device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, lds_u8 *smem, int tid, int wave, int unit,
-                                                            int nkt)
+__device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, lds_u8 *smem, int tid, int unit, int nkt)
 {
     const Args &a = g.f;
     const int kt = unit % nkt, bk = unit / nkt;
@@ -579,7 +593,7 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
     X.c32 = X.lane & 31;
     X.Mtot = a.S * a.G; // rows of this candidate
     X.c = a.scale * kLog2e;
-    X.scr = smem + wave * (kScrBytes + kDkvAux);
+    X.scr = smem + DH * (kScrBytes + kDkvAux);
     X.sv_row_lo = 4 * ((X.c32 >> 4) & 1) + ((X.c32 >> 1) & 3);
     X.sv_chunk_lo = 2 * ((X.c32 >> 3) & 1) + (X.c32 & 1);
     X.head = k;
@@ -587,14 +601,15 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
     X.P = 0;
     X.ksg = reinterpret_cast<const unsigned short *>(a.ks) + (long long)k * a.ks_sh;
     X.vsg = reinterpret_cast<const unsigned short *>(a.vs) + (long long)k * a.ks_sh;
-    Ctx Xs = X; // V rows as row-major fragments
-    Xs.ksg = X.vsg;
-    Xs.vsg = X.ksg;
     typedef __attribute__((address_space(3))) float lds_f32;
     typedef __attribute__((address_space(3))) floatx4 lds_f32x4;
     lds_f32 *aux_lse = (lds_f32 *)(X.scr + kScrBytes);
     lds_f32 *aux_drow = aux_lse + 32;
     lds_f32 *aux_i = aux_drow + 32; // suffix position of the row as a float, -1 for a row that does not count
+    // where the halves of S and dP change hands: mine to write, the other wavefront's to read
+    lds_u8 *xch = smem + kDkvWaves * (kScrBytes + kDkvAux);
+    lds_u8 *xch_mine = xch + DH * kDkvXchBytes + X.lane * 16, *xch_other = xch + (1 - DH) * kDkvXchBytes + X.lane * 16;
+    lds_f32 *xdrow = (lds_f32 *)(xch + kDkvWaves * kDkvXchBytes); // [2][32]: the halves of <dout,out>
 
     const int len = len_uniform(a, b);
     // this lane's key and where its gradients go
@@ -619,25 +634,33 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
             dv[dt][e] = 0.f;
         }
 
-    if (k0 < len) {
+    if (k0 < len) { // the same for both wavefronts of the workgroup: the barriers below are met by both
         const int kmax = len - 1;
         const unsigned short *qb = reinterpret_cast<const unsigned short *>(a.q) + (long long)b * a.q_sb + (long long)k * a.G * a.q_sh;
         const long long ob = (long long)b * a.o_sb + (long long)k * a.G * a.o_sh;
         const unsigned short *dob = reinterpret_cast<const unsigned short *>(g.dout) + ob;
         const unsigned short *outb = reinterpret_cast<const unsigned short *>(a.out) + ob;
         const int nrows = len * a.G; // rows (i, g) with i < len, in stacked order i*G + g
-        // the tile's K and V rows as row-major fragments: the same for every block of rows
-        uintx4 kf[8], vf[8];
-        load_suffix_k(a, X, b, k0, kmax, kf);
-        load_suffix_k(a, Xs, b, k0, kmax, vf);
+        // this half's columns of the tile's K and V rows as row-major fragments (rows past kmax clamped:
+        // never visible): the same for every block of rows
+        uintx4 kfh[4], vfh[4];
+        {
+            const int krow = k0 + X.c32 < kmax ? k0 + X.c32 : kmax;
+            const long long koff = (long long)b * a.ks_sb + (long long)krow * a.ks_ss + 8 * X.h + 64 * DH;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                kfh[i] = ld_global16(X.ksg + koff + 16 * i);
+                vfh[i] = ld_global16(X.vsg + koff + 16 * i);
+            }
+        }
         // the first block that holds a row with i >= k0
         for (int rl0 = (k0 * a.G) / kBlockRows * kBlockRows; rl0 < nrows; rl0 += kBlockRows) {
             // this lane's row of the block, clamped into the candidate
             const int rl = rl0 + X.c32 < nrows ? rl0 + X.c32 : nrows - 1;
             const bool rvalid = rl0 + X.c32 < nrows;
             const int ri = (int)fdiv((unsigned)rl, a.div_g), gq = rl - ri * a.G;
-            const long long qoff = (long long)ri * a.q_ss + (long long)gq * a.q_sh + 8 * X.h;
-            const long long ooff = (long long)ri * a.o_ss + (long long)gq * a.o_sh + 8 * X.h;
+            const long long qoff = (long long)ri * a.q_ss + (long long)gq * a.q_sh + 8 * X.h + 64 * DH;
+            const long long ooff = (long long)ri * a.o_ss + (long long)gq * a.o_sh + 8 * X.h + 64 * DH;
 
             floatx16 s, dp;
 #pragma unroll
@@ -645,42 +668,64 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
                 s[e] = 0.f;
                 dp[e] = 0.f;
             }
-            // everything the block needs from global memory is requested here, in one round trip
-            uintx4 qh[4], doh[4]; // this half's columns of q and dout, kept for the second products
+            // everything the block needs from global memory is requested here, in one round trip:
+            // this half's columns of q and dout, kept for the second products
+            uintx4 qh[4], doh[4];
             float drow = 0.f;
             const float lse_row = a.lse[((long long)b * a.Hq + k * a.G + gq) * a.S + ri] * kLog2e;
             {
-                uintx4 qf[8], dof[8], of[HAS_DELTA ? 1 : 8];
+                uintx4 oh[HAS_DELTA ? 1 : 4];
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks) {
-                    qf[ks] = ld_global16(qb + qoff + 16 * ks);
-                    dof[ks] = ld_global16(dob + ooff + 16 * ks);
+                for (int i = 0; i < 4; ++i) {
+                    qh[i] = ld_global16(qb + qoff + 16 * i);
+                    doh[i] = ld_global16(dob + ooff + 16 * i);
                     if constexpr (!HAS_DELTA)
-                        of[ks] = ld_global16(outb + ooff + 16 * ks);
+                        oh[i] = ld_global16(outb + ooff + 16 * i);
                 }
                 if constexpr (HAS_DELTA) // left there by the dq kernel (the clamped row is a valid one, hence written)
                     drow = g.delta[delta_index(a, b, k * a.G + gq, ri)];
+                // this half of the two sums over the columns
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
-                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qf[ks]), as_bf16x8(kf[ks]), s, 0, 0, 0);
+                for (int i = 0; i < 4; ++i)
+                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qh[i]), as_bf16x8(kfh[i]), s, 0, 0, 0);
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
-                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(dof[ks]), as_bf16x8(vf[ks]), dp, 0, 0, 0);
+                for (int i = 0; i < 4; ++i)
+                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(doh[i]), as_bf16x8(vfh[i]), dp, 0, 0, 0);
                 if constexpr (!HAS_DELTA) {
 #pragma unroll
-                    for (int ks = 0; ks < 8; ++ks)
+                    for (int i = 0; i < 4; ++i)
 #pragma unroll
                         for (int e = 0; e < 4; ++e) {
-                            drow = __builtin_fmaf(bf16_lo(dof[ks][e]), bf16_lo(of[ks][e]), drow);
-                            drow = __builtin_fmaf(bf16_hi(dof[ks][e]), bf16_hi(of[ks][e]), drow);
+                            drow = __builtin_fmaf(bf16_lo(doh[i][e]), bf16_lo(oh[i][e]), drow);
+                            drow = __builtin_fmaf(bf16_hi(doh[i][e]), bf16_hi(oh[i][e]), drow);
                         }
-                    drow += __shfl_xor(drow, 32, 64);
+                    drow += __shfl_xor(drow, 32, 64); // this wavefront's 64 columns
                 }
+            }
+            // the halves change hands
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    qh[i] = qf[4 * DH + i];
-                    doh[i] = dof[4 * DH + i];
+            for (int e4 = 0; e4 < 4; ++e4) {
+                *(lds_f32x4 *)(xch_mine + e4 * 1024) = floatx4{s[4 * e4], s[4 * e4 + 1], s[4 * e4 + 2], s[4 * e4 + 3]};
+                *(lds_f32x4 *)(xch_mine + 4096 + e4 * 1024) = floatx4{dp[4 * e4], dp[4 * e4 + 1], dp[4 * e4 + 2], dp[4 * e4 + 3]};
+            }
+            if constexpr (!HAS_DELTA)
+                if (X.h == 0)
+                    xdrow[DH * 32 + X.c32] = drow;
+            __syncthreads();
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) {
+                const floatx4 so = *(lds_f32x4 *)(xch_other + e4 * 1024), dpo = *(lds_f32x4 *)(xch_other + 4096 + e4 * 1024);
+#pragma unroll
+                for (int t2 = 0; t2 < 4; ++t2) {
+                    // the halves are added in the same order by both wavefronts (columns 0..63 first), so that
+                    // both hold the same bits of S and dP
+                    s[4 * e4 + t2] = DH == 0 ? s[4 * e4 + t2] + so[t2] : so[t2] + s[4 * e4 + t2];
+                    dp[4 * e4 + t2] = DH == 0 ? dp[4 * e4 + t2] + dpo[t2] : dpo[t2] + dp[4 * e4 + t2];
                 }
+            }
+            if constexpr (!HAS_DELTA) {
+                const float other = xdrow[(1 - DH) * 32 + X.c32];
+                drow = DH == 0 ? drow + other : other + drow;
             }
             // row quantities to LDS, then each lane fetches those of the 16 rows its elements belong to
             if (X.h == 0) {
@@ -721,6 +766,7 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
                 pv_half_from_fragments<DH>(X, doh, j, pfp[j], dv);
                 pv_half_from_fragments<DH>(X, qh, j, pfs[j], dk);
             }
+            __syncthreads(); // the other wavefront has read this block's halves before the next block's are written
         }
     }
     const bool kvalid = key < len;
@@ -731,20 +777,18 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
 }
 
 template <bool HAS_DELTA>
-__global__ __attribute__((amdgpu_flat_work_group_size(256, 256), amdgpu_waves_per_eu(2, 2)))
-void bwd_dkv_mfma_kernel(BwdArgs g, int nunits, int nkt)
+__global__ __attribute__((amdgpu_flat_work_group_size(kDkvWaves * 64, kDkvWaves * 64), amdgpu_waves_per_eu(2, 4)))
+void bwd_dkv_mfma_kernel(BwdArgs g, int nkt)
 {
     extern __shared__ __align__(16) unsigned char smem_generic[];
     lds_u8 *smem = (lds_u8 *)smem_generic;
     const int tid = threadIdx.x;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int unit2 = blockIdx.x * kDkvWaves + wave; // (unit, half of the output columns)
-    if (unit2 >= 2 * nunits) // no workgroup barrier anywhere in this kernel
-        return;
-    if (unit2 & 1)
-        bwd_dkv_unit<1, HAS_DELTA>(g, smem, tid, wave, unit2 >> 1, nkt);
+    // one unit per workgroup, one half of the output columns per wavefront (wave-uniform branch; both sides
+    // meet the same workgroup barriers the same number of times)
+    if (__builtin_amdgcn_readfirstlane(tid >> 6))
+        bwd_dkv_unit<1, HAS_DELTA>(g, smem, tid, blockIdx.x, nkt);
     else
-        bwd_dkv_unit<0, HAS_DELTA>(g, smem, tid, wave, unit2 >> 1, nkt);
+        bwd_dkv_unit<0, HAS_DELTA>(g, smem, tid, blockIdx.x, nkt);
 }
 
 } // namespace
@@ -758,14 +802,13 @@ hipError_t launch_bwd_dkv_mfma(const BwdArgs &g, hipStream_t stream)
 {
     const Args &a = g.f;
     const int nkt = (a.S + kTileKeys - 1) / kTileKeys;
-    const long long nunits = (long long)a.B * a.Hkv * nkt;
-    const unsigned grid = (unsigned)((2 * nunits + kDkvWaves - 1) / kDkvWaves);
+    const long long nunits = (long long)a.B * a.Hkv * nkt; // one workgroup each
+    if (nunits > 0x7fffffffLL)
+        return hipErrorInvalidValue;
     if (g.delta)
-        return launch_kernel(bwd_dkv_mfma_kernel<true>, dim3(grid), dim3(kDkvWaves * 64), kDkvLdsBytes, stream, g, (int)nunits,
-                           nkt);
+        return launch_kernel(bwd_dkv_mfma_kernel<true>, dim3((unsigned)nunits), dim3(kDkvWaves * 64), kDkvLdsBytes, stream, g, nkt);
     else
-        return launch_kernel(bwd_dkv_mfma_kernel<false>, dim3(grid), dim3(kDkvWaves * 64), kDkvLdsBytes, stream, g, (int)nunits,
-                           nkt);
+        return launch_kernel(bwd_dkv_mfma_kernel<false>, dim3((unsigned)nunits), dim3(kDkvWaves * 64), kDkvLdsBytes, stream, g, nkt);
 }
 
 hipError_t noalloc_scratch(void **ptr)
