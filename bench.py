@@ -26,24 +26,28 @@ PRERAMP_LAUNCHES = 300        # untimed launches right before the counted warm-u
                               # climbs from idle over roughly the first hundred launches of a run
 
 
-def kernel_source_rev() -> str:
-    """Short hash of the kernel sources: what the offline counter readings below are tied to."""
+FORWARD_SOURCES = ("pskv_internal.h", "pskv_mfma.hpp", "pskv_resident.hip", "pskv_stream.hip", "pskv_simple.hip")
+BACKWARD_SOURCES = FORWARD_SOURCES + ("pskv_bwd_mfma.hip", "pskv_bwd_simple.hip")
+
+
+def kernel_source_rev(files=FORWARD_SOURCES) -> str:
+    """Short hash of the kernel sources a set of offline counter readings is tied to (the forward
+    kernels' files for the forward table, those plus the backward kernels' for the backward table)."""
     import hashlib
     csrc = os.path.join(ROOT, "paper_2603_13420_amd", "csrc")
     h = hashlib.sha1()
-    for f in sorted(os.listdir(csrc)):
-        if f.startswith("pskv_") and f.endswith((".hip", ".hpp", ".h", ".cpp")):
-            h.update(open(os.path.join(csrc, f), "rb").read())
+    for f in files:
+        h.update(open(os.path.join(csrc, f), "rb").read())
     return h.hexdigest()[:12]
 
 
-def offline_counters(table, name, impl_auto: bool):
+def offline_counters(table, name, impl_auto: bool, files=FORWARD_SOURCES):
     """(traffic bytes, executed matrix-core flops, source note) from the offline rocprofv3 readings of
     `name`, or Nones with the reason when there are none or the kernels have changed since."""
     tr = table.get(name) if impl_auto else None
     if tr is None:
         return None, None, "no offline rocprofv3 reading for this configuration"
-    rev = kernel_source_rev()
+    rev = kernel_source_rev(files)
     if tr.get("rev") != rev:
         return None, None, (f"stale: {tr['file']} was measured on kernel sources {tr.get('rev')}, these are {rev}; "
                             "collect it again (the command is in that file)")
@@ -78,15 +82,15 @@ def alg_counts(w, suf_len, pre_len=None):
 # kernel sources they were taken on (kernel_source_rev()).  When the sources have changed since, the
 # bench line reports no traffic and says why, instead of a figure that no longer holds.
 HBM_TRAFFIC = {
-    "gqa8b_bf16": {"file": "resident_pipelined_kernel_gqa8b_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 111887253504.0, "fetch_kib": 142208.0, "fetch_scale": 2.0, "write_kib": 197632.8, "write_scale": 1.0},
-    "ldec_gqa8b_bf16": {"file": "stream_candidate_kernel_ldec_gqa8b_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 134809124864.0, "fetch_kib": 238004.4, "fetch_scale": 2.0, "write_kib": 327680.2, "write_scale": 1.0},
-    "ldec_qwen7b_bf16": {"file": "stream_candidate_kernel_ldec_qwen7b_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 116735868928.0, "fetch_kib": 180886.7, "fetch_scale": 2.0, "write_kib": 286720.0, "write_scale": 1.0},
-    "longprefix_bf16": {"file": "stream_pipelined_kernel_longprefix_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 279172874240.0, "fetch_kib": 62930.4, "fetch_scale": 2.0, "write_kib": 66569.8, "write_scale": 1.0},
-    "mha13b_bf16": {"file": "stream_pipelined_kernel_mha13b_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 3004086353920.0, "fetch_kib": 3937667.2, "fetch_scale": 2.0, "write_kib": 2622464.0, "write_scale": 1.0},
-    "mha7b_bf16": {"file": "resident_general_kernel_mha7b_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 34359738368.0, "fetch_kib": 129183.0, "fetch_scale": 2.0, "write_kib": 81920.8, "write_scale": 1.0},
-    "multi32_gqa8b_bf16": {"file": "resident_pipelined_kernel_multi32_gqa8b_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 85198897152.0, "fetch_kib": 151814.5, "fetch_scale": 2.0, "write_kib": 197632.0, "write_scale": 1.0},
-    "multi4_long_bf16": {"file": "stream_pipelined_kernel_multi4_long_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 73014444032.0, "fetch_kib": 60179.9, "fetch_scale": 2.0, "write_kib": 66560.0, "write_scale": 1.0},
-    "multi8_gqa8b_bf16": {"file": "resident_pipelined_kernel_multi8_gqa8b_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 93021274112.0, "fetch_kib": 142292.6, "fetch_scale": 2.0, "write_kib": 197632.0, "write_scale": 1.0},
+    "gqa8b_bf16": {"file": "resident_pipelined_kernel_gqa8b_bf16_hbm_traffic.txt", "rev": "8c7521a516eb", "mfma_flops": 111887253504.0, "fetch_kib": 142208.0, "fetch_scale": 2.0, "write_kib": 197632.8, "write_scale": 1.0},
+    "ldec_gqa8b_bf16": {"file": "stream_candidate_kernel_ldec_gqa8b_bf16_hbm_traffic.txt", "rev": "8c7521a516eb", "mfma_flops": 134809124864.0, "fetch_kib": 238004.4, "fetch_scale": 2.0, "write_kib": 327680.2, "write_scale": 1.0},
+    "ldec_qwen7b_bf16": {"file": "stream_candidate_kernel_ldec_qwen7b_bf16_hbm_traffic.txt", "rev": "8c7521a516eb", "mfma_flops": 116735868928.0, "fetch_kib": 180886.7, "fetch_scale": 2.0, "write_kib": 286720.0, "write_scale": 1.0},
+    "longprefix_bf16": {"file": "stream_pipelined_kernel_longprefix_bf16_hbm_traffic.txt", "rev": "8c7521a516eb", "mfma_flops": 279172874240.0, "fetch_kib": 62930.4, "fetch_scale": 2.0, "write_kib": 66569.8, "write_scale": 1.0},
+    "mha13b_bf16": {"file": "stream_pipelined_kernel_mha13b_bf16_hbm_traffic.txt", "rev": "8c7521a516eb", "mfma_flops": 3004086353920.0, "fetch_kib": 3937667.2, "fetch_scale": 2.0, "write_kib": 2622464.0, "write_scale": 1.0},
+    "mha7b_bf16": {"file": "resident_general_kernel_mha7b_bf16_hbm_traffic.txt", "rev": "8c7521a516eb", "mfma_flops": 34359738368.0, "fetch_kib": 129183.0, "fetch_scale": 2.0, "write_kib": 81920.8, "write_scale": 1.0},
+    "multi32_gqa8b_bf16": {"file": "resident_pipelined_kernel_multi32_gqa8b_bf16_hbm_traffic.txt", "rev": "8c7521a516eb", "mfma_flops": 85198897152.0, "fetch_kib": 151814.5, "fetch_scale": 2.0, "write_kib": 197632.0, "write_scale": 1.0},
+    "multi4_long_bf16": {"file": "stream_pipelined_kernel_multi4_long_bf16_hbm_traffic.txt", "rev": "8c7521a516eb", "mfma_flops": 73014444032.0, "fetch_kib": 60179.9, "fetch_scale": 2.0, "write_kib": 66560.0, "write_scale": 1.0},
+    "multi8_gqa8b_bf16": {"file": "resident_pipelined_kernel_multi8_gqa8b_bf16_hbm_traffic.txt", "rev": "8c7521a516eb", "mfma_flops": 93021274112.0, "fetch_kib": 142292.6, "fetch_scale": 2.0, "write_kib": 197632.0, "write_scale": 1.0},
 }
 
 
@@ -134,7 +138,7 @@ def cpu_baseline_multi(inp, budget_s=12.0):
 
 # The same for one backward call (its two kernels together).
 HBM_TRAFFIC_BWD = {
-    "gqa8b_bf16": {"file": "bwd_kernels_gqa8b_bf16_hbm_traffic.txt", "rev": "0dc3a7ab76f7", "mfma_flops": 205126631424.0, "fetch_kib": 510963.4, "fetch_scale": 2.0, "write_kib": 297560.5, "write_scale": 1.0},
+    "gqa8b_bf16": {"file": "bwd_kernels_gqa8b_bf16_hbm_traffic.txt", "rev": "203f5e25f161", "mfma_flops": 192694714368.0, "fetch_kib": 510872.3, "fetch_scale": 2.0, "write_kib": 301673.8, "write_scale": 1.0},
 }
 
 
@@ -204,7 +208,7 @@ def bench_backward(args):
            "alg_bytes_per_step": bytes_}
     hbm["frac"] = hbm["achieved"] / hbm["peak"]
     roof, other = (hbm, compute) if bytes_ / (PEAK_HBM_GBS * 1e9) >= flops / (compute["peak"] * 1e12) else (compute, hbm)
-    roof["traffic"], _, roof["traffic_source"] = offline_counters(HBM_TRAFFIC_BWD, w.name, args.impl == "auto")
+    roof["traffic"], _, roof["traffic_source"] = offline_counters(HBM_TRAFFIC_BWD, w.name, args.impl == "auto", BACKWARD_SOURCES)
     roof["traffic_unit"] = "bytes per step"
     roof["kernel_ms"] = kern_ms
     line = {"metric": "candidate suffixes/sec per attention layer, backward pass", "value": w.B / (ms_per_step * 1e-3),
