@@ -170,8 +170,10 @@ struct Stager {
     int last;                           // index of the last tile
 };
 
-// One 16-byte request per lane straight into LDS: lane l's bytes land at lds_base + 16*l (lds_base
-// is the same for the whole wavefront).  Written as an instruction rather than through the
+// One 16-byte request per lane straight into LDS: lane l's bytes, fetched from gbase + voff (gbase
+// the same for the whole wavefront and held in scalar registers, voff the lane's own 32-bit
+// offset), land at lds_base + 16*l (lds_base is the same for the whole wavefront).
+// Written as an instruction rather than through the
 // compiler's builtin: the compiler would make every later LDS read wait for all such requests
 // still in flight.  Its own bookkeeping of the vector memory counter stays on the safe side:
 // requests it does not know of can only make its waits longer.  M0 carries the LDS address and
@@ -180,10 +182,11 @@ struct Stager {
 // reserved register, never allocated, which is all the warning silenced here has to say.)
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"
-__device__ inline void request_to_lds(const unsigned char *g, lds_u8 *lds_base)
+__device__ inline void request_to_lds(const unsigned char *gbase, unsigned voff, lds_u8 *lds_base)
 {
     const unsigned lds_addr = (unsigned)(unsigned long long)lds_base;
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr), "v"(g) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(gbase)
+                 : "memory", "m0");
 }
 #pragma clang diagnostic pop
 // s_waitcnt immediate (gfx9 encoding): vector memory counter at most n (n < 16), the others untouched
@@ -205,8 +208,8 @@ void stream_pipelined_kernel(Args a, int npasses)
     auto request = [&](const Stager &g, int kt) {
         const unsigned base = (unsigned)kt * g.tile_stride;
         lds_u8 *slot = smem + (kt & (kRing - 1)) * kSlotBytes + wave * 1024;
-        request_to_lds(g.kbase + (base + (kt == g.last ? g.k_off_last : g.k_off)), slot);
-        request_to_lds(g.vbase + (base + (kt == g.last ? g.v_off_last : g.v_off)), slot + kTileBytes);
+        request_to_lds(g.kbase + base, kt == g.last ? g.k_off_last : g.k_off, slot);
+        request_to_lds(g.vbase + base, kt == g.last ? g.v_off_last : g.v_off, slot + kTileBytes);
     };
 
     Stager g;
@@ -218,9 +221,9 @@ void stream_pipelined_kernel(Args a, int npasses)
     bool wg_bad = false;
     int p = blockIdx.x;
     Pass ps = make_pass(a, p, npasses, nblocks, wave);
-    Row nxt = decode_row(a, X, ps.blk, ps.head, ps.cand0);
+    BlockRows nxt = decode_block(a, X, ps.blk, ps.head, ps.cand0);
     uintx4 q[8]; // this pass's Q fragments until their last use, then the next pass's
-    load_q(a, X, nxt, q);
+    load_q_block(a, X, nxt, q);
 
     bool wg_short = false;
     while (p < npasses) {
@@ -230,8 +233,8 @@ void stream_pipelined_kernel(Args a, int npasses)
             wg_short = true;
             p += gridDim.x;
             ps = make_pass(a, p, npasses, nblocks, wave);
-            nxt = decode_row(a, X, ps.blk, ps.head, ps.cand0);
-            load_q(a, X, nxt, q);
+            nxt = decode_block(a, X, ps.blk, ps.head, ps.cand0);
+            load_q_block(a, X, nxt, q);
             continue;
         }
         {
@@ -245,8 +248,8 @@ void stream_pipelined_kernel(Args a, int npasses)
         }
         const int blk = ps.blk, r0 = blk * kBlockRows;
         const bool active = ps.active;
-        const Row row = nxt;
-        const bool rvalid = active && row.rin && (int)row.ri < clamp_len(a, row.rlen);
+        const BlockRows row = nxt;
+        const bool rvalid = active && row.ri < row.len;
 
         // The ring is free here: the barrier that ended the previous pass was passed only by
         // wavefronts that had finished reading it.  Tiles 0..6 are requested at once; the first
@@ -275,10 +278,9 @@ void stream_pipelined_kernel(Args a, int npasses)
         };
 
         // the block's suffix: candidate sb, keys 0..skmax
-        const int sb = (int)fdiv(fdiv(r0, a.div_g), a.div_s);
-        const int i_hi = (int)fdiv(r0 + kBlockRows - 1, a.div_g) - sb * a.S;
-        const int len = len_uniform(a, X.cand0 + sb);
-        const int skmax = i_hi < len - 1 ? i_hi : len - 1;
+        const int i_hi = (int)fdiv(r0 + kBlockRows - 1, a.div_g) - (row.b - X.cand0) * a.S;
+        const int skmax = i_hi < row.len - 1 ? i_hi : row.len - 1;
+        const int skld = skmax > 0 ? skmax : 0; // row the suffix loads are clamped to (a candidate may be empty)
 
         // ---- first prefix tile: scores, reference maximum ----
         floatx16 sA, sB; // raw scores of the current and of the next tile, roles alternating
@@ -327,11 +329,11 @@ void stream_pipelined_kernel(Args a, int npasses)
         // steps from here, are requested once the staging registers are free.
         if (t + 1 <= T - 2) {
             pair_top(t);
-            load_suffix_k(a, X, X.cand0 + sb, 0, skmax, skf);
+            load_suffix_k_block(a, X, row.b, 0, skld, skf);
             PSKV_STEP_PAIR(t);
             t += 2;
         } else {
-            load_suffix_k(a, X, X.cand0 + sb, 0, skmax, skf);
+            load_suffix_k_block(a, X, row.b, 0, skld, skf);
         }
 #undef PSKV_STEP_PAIR
         if (t <= T - 2) { // one step left over: do it and put scores and weights back in their places
@@ -348,7 +350,7 @@ void stream_pipelined_kernel(Args a, int npasses)
                 if (8 * (e >> 2) + (e & 3) >= nv)
                     sA[e] = -INFINITY;
         }
-        load_suffix_v(a, X, X.cand0 + sb, 0, skmax, svf); // one step ahead of its use
+        load_suffix_v_block(a, X, row.b, 0, skld, svf); // one step ahead of its use
         // ---- last prefix tile: the "next scores" are those of the first suffix step ----
         pipe_tile<true, true, true, false, false, false, true>(kimg(0), skf, vimg(T - 2), kimg(0), vimg(T - 1), pre, q, sA,
                                                                sB, X.c, m, 0, l, pB, pA, o);
@@ -356,36 +358,51 @@ void stream_pipelined_kernel(Args a, int npasses)
         // the next pass of this workgroup (clamped past the end: requested unconditionally)
         p += gridDim.x;
         ps = make_pass(a, p, npasses, nblocks, wave);
-        if (ONE_STEP) { // Q has been used for the last time: the next pass's Q takes its place
-            nxt = decode_row(a, X, ps.blk, ps.head, ps.cand0);
-            load_q(a, X, nxt, q);
+        // Without further suffix steps (always so when S <= 32) Q has been used for the last time:
+        // the next pass's Q takes its place.
+        const bool more = !ONE_STEP && skmax >= kTileKeys;
+        if (!more) {
+            nxt = decode_block(a, X, ps.blk, ps.head, ps.cand0);
+            load_q_block(a, X, nxt, q);
         }
 
         // ---- first suffix step: causal mask and weights under the value product of the last
         //      prefix tile; then its own value product through the scratch tile ----
         pipe_tile<false, false, true, false, true, false, false>(kimg(0), skf, vimg(T - 1), kimg(0), vimg(0), pre, q, sB, sB,
-                                                                 X.c, m, (int)row.ri - 4 * X.h, l, pA, pB, o);
+                                                                 X.c, m, row.ri - 4 * X.h, l, pA, pB, o);
         pv_from_scratch(X, svf[0], as_bf16x8(pB[0]), o);
         pv_from_scratch(X, svf[1], as_bf16x8(pB[1]), o);
-        if (!ONE_STEP) {
-            for (int k0 = kTileKeys; k0 <= skmax; k0 += kTileKeys) {
-                load_suffix_k(a, X, X.cand0 + sb, k0, skmax, skf);
-                load_suffix_v(a, X, X.cand0 + sb, k0, skmax, svf);
+        if (more) {
+            // The second suffix step's K and V and, in the same round trip to memory, the next
+            // pass's Q (into registers of its own: this pass's Q is still needed for the scores).
+            uintx4 qn[8];
+            load_suffix_k_block(a, X, row.b, kTileKeys, skmax, skf);
+            load_suffix_v_block(a, X, row.b, kTileKeys, skmax, svf);
+            nxt = decode_block(a, X, ps.blk, ps.head, ps.cand0);
+            load_q_block(a, X, nxt, qn);
+            for (int k0 = kTileKeys;; k0 += kTileKeys) {
 #pragma unroll
                 for (int e = 0; e < 16; ++e)
                     sB[e] = 0.f;
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks)
                     sB = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(skf[ks]), as_bf16x8(q[ks]), sB, 0, 0, 0);
-                suffix_step_fixed(X, (int)row.ri, k0, sB, m, l, svf, o);
+                const bool again = k0 + kTileKeys <= skmax;
+                if (again)
+                    load_suffix_k_block(a, X, row.b, k0 + kTileKeys, skmax, skf);
+                suffix_step_fixed(X, row.ri, k0, sB, m, l, svf, o);
+                if (!again)
+                    break;
+                load_suffix_v_block(a, X, row.b, k0 + kTileKeys, skmax, svf);
             }
-            nxt = decode_row(a, X, ps.blk, ps.head, ps.cand0);
-            load_q(a, X, nxt, q);
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks)
+                q[ks] = qn[ks];
         }
 
         const bool bad = __builtin_amdgcn_ballot_w64(rvalid && !(l < kBig)) != 0;
         if (active)
-            store_block(a, X, r0, row, rvalid, m, l, o);
+            store_block_rows(a, X, row, m, l, o);
         // the wavefront's verdict goes into the first word of its own scratch tile
         if (X.lane == 0)
             *(lds_int *)X.scr = bad ? 1 : 0;
@@ -791,7 +808,7 @@ hipError_t launch_stream(const Args &a, hipStream_t stream)
     const long long npasses = ((rows + kPassRows - 1) / kPassRows) * a.Np * a.Hkv;
     const unsigned grid = (unsigned)(npasses < num_cu ? npasses : num_cu);
     const bool pipelined = ((long long)a.S * a.G) % kBlockRows == 0 && max_tiles >= kMinTiles &&
-                           (long long)a.P * a.kp_sp * 2 < 0x7fffffffLL;
+                           (long long)a.P * a.kp_sp * 2 < 0x7fffffffLL && block_offsets_fit(a);
     // Long suffix-side segments whose candidates fill most of a workgroup's eight wavefronts
     // take the candidate passes.
     if (pipelined && a.S > kTileKeys && (long long)a.S * a.ks_ss * 2 < 0x7fffffffLL) {
