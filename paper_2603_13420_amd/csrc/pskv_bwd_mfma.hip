@@ -505,85 +505,63 @@ void bwd_dq_resident_kernel(BwdArgs g, int per_vh, int vh_slots, int max_tiles)
 //     dK^T += Q^T dS       A = Q^T through the scratch tile,   B = dS packed to bf16
 // The first two products contract over the 128 columns: each wavefront forms its own half of that
 // sum from its own half of the columns of q, dout, K and V - the only columns it ever fetches, so
-// that every row of q and dout crosses HBM once per tile and not once per wavefront - and the two
-// halves of S and dP (4 KB each, fp32) change hands through LDS.  The second products need exactly
-// the columns the wavefront already holds.
+// that every row of q and dout crosses HBM once per tile and not once per wavefront - and the
+// halves change hands through LDS: a wavefront completes S and dP, and takes the exponentials,
+// for one of the block's two 16-row steps only (it receives the other wavefront's half of the
+// sums for those rows, 2 KB each of S and dP in fp32) and passes that step's packed P and dS on
+// to the other one.  The second products need exactly the columns the wavefront already holds.
 // The accumulators of S hold, for lane half h, rows 8*kk + 4*h + t of the block in element
 // 4*kk + t: exactly the order in which the scratch image hands out the rows of dO and Q, so P
 // and dS go from the first products to the second ones through registers only.
 // ------------------------------------------------------------------------------------------
 constexpr int kDkvWaves = 2; // the two column halves of one unit
+constexpr int kDkvScrBytes = 4 * 2048; // per wavefront: the four images dO and Q are transposed through (the first 4 KB also
+                                       // serve the final store)
 constexpr int kDkvAux = 512; // per wavefront: lse, <dout,out> and suffix position of the block's 32 rows
-constexpr int kDkvXchBytes = 2 * 16 * 256; // per wavefront: its halves of S and dP, 16 accumulator registers of 256 bytes each
-constexpr int kDkvLdsBytes = kDkvWaves * (kScrBytes + kDkvAux + kDkvXchBytes) + 256; // + the halves of <dout,out>
+constexpr int kDkvXchBytes = 2 * 8 * 256 + 2 * 1024; // per wavefront, for the other one: its halves of S and dP for that one's
+                                                     // 16-row step (8 accumulator registers of 256 bytes each), then its own
+                                                     // step's packed weights and score gradients
+constexpr int kDkvLdsBytes = kDkvWaves * (kDkvScrBytes + kDkvAux + kDkvXchBytes) + 256; // + the halves of <dout,out>
 
-// O^T-style accumulation of two 32-column groups (dt = 2*DH, 2*DH+1) for one 16-row step whose
-// rows are in registers in scratch-image order: through the scratch tile (cf. pv_from_scratch).
-template <int DH>
-__device__ inline void pv_half_from_scratch(const Ctx &X, const uintx4 (&vstep)[2], bf16x8 pfj, floatx16 (&o)[2])
+// dO^T and Q^T of a 32-row block as A operands of the second products, from the row-major
+// fragments the lanes hold for the first ones (lane (row c32, half h): columns 16*i + 8*h ..+7 of
+// this wavefront's 64 in frag[i]).  Each lane puts its chunks where a scratch image wants them -
+// four images of 2 KB, one per (16-row step j, tensor): chunk (row r, columns 16*i + 8*h) belongs
+// to fragment (i/2, u = (r/8)%2), slot pair 16*((r/4)%2) + 8*(i%2) + 2*(r%4) + h - and the
+// transposing reads hand them back: at[j][w][i2] is the A fragment of step j, tensor w (0: dO,
+// 1: Q), 32-column group i2 of the wavefront's half.  All of it is written, then all of it read:
+// nothing here depends on the weights, so the whole exchange runs under the first products.
+__device__ inline void transpose_halves(const Ctx &X, const uintx4 (&doh)[4], const uintx4 (&qh)[4], bf16x8 (&at)[2][2][2])
 {
+    const int j = X.c32 >> 4, u = (X.c32 >> 3) & 1;
+    lds_u8 *dst = X.scr + j * 4096 + u * 512 + (16 * ((X.c32 >> 2) & 1) + 2 * (X.c32 & 3) + X.h) * 16;
 #pragma unroll
-    for (int i2 = 0; i2 < 2; ++i2)
-        *(lds_u128 *)(X.scr + (2 * DH + i2) * 1024 + X.lane * 16) = vstep[i2];
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    bf16x8 va[2];
-#pragma unroll
-    for (int i2 = 0; i2 < 2; ++i2) {
-        const int dt = 2 * DH + i2;
-        short4v lo = lds_read_tr(X.scr + X.lane * 8 + (dt * 2 + 0) * 512);
-        short4v hi = lds_read_tr(X.scr + X.lane * 8 + (dt * 2 + 1) * 512);
-        short8v v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        __builtin_memcpy(&va[i2], &v8, 16);
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int i2 = 0; i2 < 2; ++i2)
-        o[i2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i2], pfj, o[i2], 0, 0, 0);
-}
-
-// The same accumulation for the 16-row step j of a 32-row block whose rows the lanes already hold
-// as row-major fragments (lane (row c32, half h): columns 16*ks + 8*h ..+7 in frag[ks - 4*DH] for the
-// four ks of this half of the columns): the lanes that own rows of step j put their chunks where
-// the scratch image wants them - chunk (row r, columns 16*ks + 8*h) belongs to fragment
-// (dt = ks/2, u = (r/8)%2), slot pair 16*((r/4)%2) + 8*(ks%2) + 2*(r%4) + h - and the transposing
-// read hands them back as A fragments.
-template <int DH>
-__device__ inline void pv_half_from_fragments(const Ctx &X, const uintx4 (&frag)[4], int j, bf16x8 pfj, floatx16 (&o)[2])
-{
-    if ((X.c32 >> 4) == j) {
-        const int u = (X.c32 >> 3) & 1;
-        lds_u8 *dst = X.scr + u * 512 + (16 * ((X.c32 >> 2) & 1) + 2 * (X.c32 & 3) + X.h) * 16;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int ks = 4 * DH + i;
-            *(lds_u128 *)(dst + (ks >> 1) * 1024 + (ks & 1) * 128) = frag[i];
-        }
+    for (int i = 0; i < 4; ++i) {
+        *(lds_u128 *)(dst + (i >> 1) * 1024 + (i & 1) * 128) = doh[i];
+        *(lds_u128 *)(dst + 2048 + (i >> 1) * 1024 + (i & 1) * 128) = qh[i];
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-    bf16x8 va[2];
 #pragma unroll
-    for (int i2 = 0; i2 < 2; ++i2) {
-        const int dt = 2 * DH + i2;
-        short4v lo = lds_read_tr(X.scr + X.lane * 8 + (dt * 2 + 0) * 512);
-        short4v hi = lds_read_tr(X.scr + X.lane * 8 + (dt * 2 + 1) * 512);
-        short8v v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        __builtin_memcpy(&va[i2], &v8, 16);
-    }
+    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int w = 0; w < 2; ++w)
+#pragma unroll
+            for (int i2 = 0; i2 < 2; ++i2) {
+                const lds_u8 *img = X.scr + (2 * jj + w) * 2048 + X.lane * 8;
+                short4v lo = lds_read_tr(const_cast<lds_u8 *>(img) + (i2 * 2 + 0) * 512);
+                short4v hi = lds_read_tr(const_cast<lds_u8 *>(img) + (i2 * 2 + 1) * 512);
+                short8v v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                __builtin_memcpy(&at[jj][w][i2], &v8, 16);
+            }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int i2 = 0; i2 < 2; ++i2)
-        o[i2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i2], pfj, o[i2], 0, 0, 0);
 }
 
 template <int DH, bool HAS_DELTA>
-__device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, lds_u8 *smem, int tid, int unit, int nkt)
+__device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, lds_u8 *smem, int tid, int bk, int kt)
 {
     const Args &a = g.f;
-    const int kt = unit % nkt, bk = unit / nkt;
     const int k = bk % a.Hkv, b = bk / a.Hkv;
     const int k0 = kt * kTileKeys;
 
@@ -593,7 +571,7 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
     X.c32 = X.lane & 31;
     X.Mtot = a.S * a.G; // rows of this candidate
     X.c = a.scale * kLog2e;
-    X.scr = smem + DH * (kScrBytes + kDkvAux);
+    X.scr = smem + DH * (kDkvScrBytes + kDkvAux);
     X.sv_row_lo = 4 * ((X.c32 >> 4) & 1) + ((X.c32 >> 1) & 3);
     X.sv_chunk_lo = 2 * ((X.c32 >> 3) & 1) + (X.c32 & 1);
     X.head = k;
@@ -603,28 +581,16 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
     X.vsg = reinterpret_cast<const unsigned short *>(a.vs) + (long long)k * a.ks_sh;
     typedef __attribute__((address_space(3))) float lds_f32;
     typedef __attribute__((address_space(3))) floatx4 lds_f32x4;
-    lds_f32 *aux_lse = (lds_f32 *)(X.scr + kScrBytes);
+    lds_f32 *aux_lse = (lds_f32 *)(X.scr + kDkvScrBytes);
     lds_f32 *aux_drow = aux_lse + 32;
     lds_f32 *aux_i = aux_drow + 32; // suffix position of the row as a float, -1 for a row that does not count
     // where the halves of S and dP change hands: mine to write, the other wavefront's to read
-    lds_u8 *xch = smem + kDkvWaves * (kScrBytes + kDkvAux);
+    lds_u8 *xch = smem + kDkvWaves * (kDkvScrBytes + kDkvAux);
     lds_u8 *xch_mine = xch + DH * kDkvXchBytes + X.lane * 16, *xch_other = xch + (1 - DH) * kDkvXchBytes + X.lane * 16;
     lds_f32 *xdrow = (lds_f32 *)(xch + kDkvWaves * kDkvXchBytes); // [2][32]: the halves of <dout,out>
 
     const int len = len_uniform(a, b);
-    // this lane's key and where its gradients go
-    const int key = k0 + X.c32;
-    unsigned short *dst_k[4], *dst_v[4];
-    bool dst_ok[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int jr = k0 + 8 * u + (X.lane >> 3);
-        dst_ok[u] = jr < a.S;
-        const long long off = (long long)b * a.ks_sb + (long long)(dst_ok[u] ? jr : 0) * a.ks_ss + (long long)k * a.ks_sh +
-                              8 * (X.lane & 7);
-        dst_k[u] = reinterpret_cast<unsigned short *>(g.dk) + off;
-        dst_v[u] = reinterpret_cast<unsigned short *>(g.dv) + off;
-    }
+    const int key = k0 + X.c32; // this lane's key
     floatx16 dk[2], dv[2]; // output columns 64*DH .. 64*DH+63
 #pragma unroll
     for (int dt = 0; dt < 2; ++dt)
@@ -653,14 +619,64 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
                 vfh[i] = ld_global16(X.vsg + koff + 16 * i);
             }
         }
-        // the first block that holds a row with i >= k0
-        for (int rl0 = (k0 * a.G) / kBlockRows * kBlockRows; rl0 < nrows; rl0 += kBlockRows) {
-            // this lane's row of the block, clamped into the candidate
+        // What a block needs from global memory, all requested in one round trip: this half's columns
+        // of q and dout (kept for the second products) and the row quantities of this lane's row of
+        // the block, clamped into the candidate.
+        struct BlockIn {
+            uintx4 qh[4], doh[4];
+            float lse_row, drow;
+            int ri;
+            bool rvalid;
+        };
+        auto fetch = [&](int rl0, BlockIn &x, uintx4 (&oh)[HAS_DELTA ? 1 : 4]) {
             const int rl = rl0 + X.c32 < nrows ? rl0 + X.c32 : nrows - 1;
-            const bool rvalid = rl0 + X.c32 < nrows;
-            const int ri = (int)fdiv((unsigned)rl, a.div_g), gq = rl - ri * a.G;
-            const long long qoff = (long long)ri * a.q_ss + (long long)gq * a.q_sh + 8 * X.h + 64 * DH;
-            const long long ooff = (long long)ri * a.o_ss + (long long)gq * a.o_sh + 8 * X.h + 64 * DH;
+            x.rvalid = rl0 + X.c32 < nrows;
+            x.ri = (int)fdiv((unsigned)rl, a.div_g);
+            const int gq = rl - x.ri * a.G;
+            const long long qoff = (long long)x.ri * a.q_ss + (long long)gq * a.q_sh + 8 * X.h + 64 * DH;
+            const long long ooff = (long long)x.ri * a.o_ss + (long long)gq * a.o_sh + 8 * X.h + 64 * DH;
+            x.lse_row = a.lse[((long long)b * a.Hq + k * a.G + gq) * a.S + x.ri];
+            x.drow = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                x.qh[i] = ld_global16(qb + qoff + 16 * i);
+                x.doh[i] = ld_global16(dob + ooff + 16 * i);
+                if constexpr (!HAS_DELTA)
+                    oh[i] = ld_global16(outb + ooff + 16 * i);
+            }
+            if constexpr (HAS_DELTA) // left there by the dq kernel (the clamped row is a valid one, hence written)
+                x.drow = g.delta[delta_index(a, b, k * a.G + gq, x.ri)];
+        };
+        // The blocks that hold a row with i >= k0, from the candidate's last block down to the first
+        // such one: the units of one (candidate, KV head) pair run side by side on one XCD (see the
+        // kernel), and walking downwards they all ask for the same rows of q and dout at about the same
+        // time, whatever their tile, so that those rows come from HBM once and from that XCD's L2 after.
+        const int rl_first = (k0 * a.G) / kBlockRows * kBlockRows;
+        const int rl_last = (nrows - 1) / kBlockRows * kBlockRows;
+        // With <dout,out> at hand (no rows of out to fetch) there are registers to spare: the next
+        // block is requested while the current one is worked on.
+        constexpr bool kAhead = HAS_DELTA;
+        BlockIn nx;
+        uintx4 oh[HAS_DELTA ? 1 : 4];
+        if constexpr (kAhead) {
+            fetch(rl_last, nx, oh);
+            __builtin_amdgcn_s_waitcnt(0x0F70); // nothing in flight at the loop's entry either (see its end)
+        }
+        for (int rl0 = rl_last; rl0 >= rl_first; rl0 -= kBlockRows) {
+            BlockIn cur;
+            if constexpr (kAhead) {
+                cur = nx;
+                if (rl0 - kBlockRows >= rl_first)
+                    fetch(rl0 - kBlockRows, nx, oh);
+            } else {
+                fetch(rl0, cur, oh);
+            }
+            const uintx4 (&qh)[4] = cur.qh;
+            const uintx4 (&doh)[4] = cur.doh;
+            const bool rvalid = cur.rvalid;
+            const int ri = cur.ri;
+            const float lse_row = cur.lse_row * kLog2e;
+            float drow = cur.drow;
 
             floatx16 s, dp;
 #pragma unroll
@@ -668,66 +684,57 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
                 s[e] = 0.f;
                 dp[e] = 0.f;
             }
-            // everything the block needs from global memory is requested here, in one round trip:
-            // this half's columns of q and dout, kept for the second products
-            uintx4 qh[4], doh[4];
-            float drow = 0.f;
-            const float lse_row = a.lse[((long long)b * a.Hq + k * a.G + gq) * a.S + ri] * kLog2e;
-            {
-                uintx4 oh[HAS_DELTA ? 1 : 4];
+            // dO^T and Q^T for the second products (independent of what follows: under the first products)
+            bf16x8 at[2][2][2];
+            transpose_halves(X, doh, qh, at);
+            // this half of the two sums over the columns
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    qh[i] = ld_global16(qb + qoff + 16 * i);
-                    doh[i] = ld_global16(dob + ooff + 16 * i);
-                    if constexpr (!HAS_DELTA)
-                        oh[i] = ld_global16(outb + ooff + 16 * i);
-                }
-                if constexpr (HAS_DELTA) // left there by the dq kernel (the clamped row is a valid one, hence written)
-                    drow = g.delta[delta_index(a, b, k * a.G + gq, ri)];
-                // this half of the two sums over the columns
+            for (int i = 0; i < 4; ++i)
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qh[i]), as_bf16x8(kfh[i]), s, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(doh[i]), as_bf16x8(vfh[i]), dp, 0, 0, 0);
+            if constexpr (!HAS_DELTA) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(qh[i]), as_bf16x8(kfh[i]), s, 0, 0, 0);
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(doh[i]), as_bf16x8(vfh[i]), dp, 0, 0, 0);
-                if constexpr (!HAS_DELTA) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            drow = __builtin_fmaf(bf16_lo(doh[i][e]), bf16_lo(oh[i][e]), drow);
-                            drow = __builtin_fmaf(bf16_hi(doh[i][e]), bf16_hi(oh[i][e]), drow);
-                        }
-                    drow += __shfl_xor(drow, 32, 64); // this wavefront's 64 columns
-                }
+                    for (int e = 0; e < 4; ++e) {
+                        drow = __builtin_fmaf(bf16_lo(doh[i][e]), bf16_lo(oh[i][e]), drow);
+                        drow = __builtin_fmaf(bf16_hi(doh[i][e]), bf16_hi(oh[i][e]), drow);
+                    }
+                drow += __shfl_xor(drow, 32, 64); // this wavefront's 64 columns
             }
-            // the halves change hands
+            // The halves change hands.  Each wavefront completes S and dP for one of the block's two
+            // 16-row steps only (wavefront DH: rows 16*DH .. 16*DH+15, accumulator elements 8*DH .. 8*DH+7):
+            // it hands over its half of the other step's sums and later receives that step's finished
+            // weights, so that the exponentials are taken once per element and not once per wavefront.
 #pragma unroll
-            for (int e4 = 0; e4 < 4; ++e4) {
-                *(lds_f32x4 *)(xch_mine + e4 * 1024) = floatx4{s[4 * e4], s[4 * e4 + 1], s[4 * e4 + 2], s[4 * e4 + 3]};
-                *(lds_f32x4 *)(xch_mine + 4096 + e4 * 1024) = floatx4{dp[4 * e4], dp[4 * e4 + 1], dp[4 * e4 + 2], dp[4 * e4 + 3]};
+            for (int i2 = 0; i2 < 2; ++i2) {
+                const int e0 = 4 * (2 * (1 - DH) + i2); // elements of the other wavefront's step
+                *(lds_f32x4 *)(xch_mine + i2 * 1024) = floatx4{s[e0], s[e0 + 1], s[e0 + 2], s[e0 + 3]};
+                *(lds_f32x4 *)(xch_mine + 2048 + i2 * 1024) = floatx4{dp[e0], dp[e0 + 1], dp[e0 + 2], dp[e0 + 3]};
             }
             if constexpr (!HAS_DELTA)
                 if (X.h == 0)
                     xdrow[DH * 32 + X.c32] = drow;
             __syncthreads();
+            float sf[8], dpf[8];
 #pragma unroll
-            for (int e4 = 0; e4 < 4; ++e4) {
-                const floatx4 so = *(lds_f32x4 *)(xch_other + e4 * 1024), dpo = *(lds_f32x4 *)(xch_other + 4096 + e4 * 1024);
+            for (int i2 = 0; i2 < 2; ++i2) {
+                const int e0 = 4 * (2 * DH + i2);
+                const floatx4 so = *(lds_f32x4 *)(xch_other + i2 * 1024), dpo = *(lds_f32x4 *)(xch_other + 2048 + i2 * 1024);
 #pragma unroll
                 for (int t2 = 0; t2 < 4; ++t2) {
-                    // the halves are added in the same order by both wavefronts (columns 0..63 first), so that
-                    // both hold the same bits of S and dP
-                    s[4 * e4 + t2] = DH == 0 ? s[4 * e4 + t2] + so[t2] : so[t2] + s[4 * e4 + t2];
-                    dp[4 * e4 + t2] = DH == 0 ? dp[4 * e4 + t2] + dpo[t2] : dpo[t2] + dp[4 * e4 + t2];
+                    // the halves are added in a fixed order (columns 0..63 first), whichever wavefront does it
+                    sf[4 * i2 + t2] = DH == 0 ? s[e0 + t2] + so[t2] : so[t2] + s[e0 + t2];
+                    dpf[4 * i2 + t2] = DH == 0 ? dp[e0 + t2] + dpo[t2] : dpo[t2] + dp[e0 + t2];
                 }
             }
             if constexpr (!HAS_DELTA) {
                 const float other = xdrow[(1 - DH) * 32 + X.c32];
                 drow = DH == 0 ? drow + other : other + drow;
             }
-            // row quantities to LDS, then each lane fetches those of the 16 rows its elements belong to
+            // row quantities to LDS, then each lane fetches those of the 8 rows its elements of this step belong to
             if (X.h == 0) {
                 aux_lse[X.c32] = lse_row;
                 aux_drow[X.c32] = drow;
@@ -735,41 +742,65 @@ __device__ __attribute__((always_inline)) void bwd_dkv_unit(const BwdArgs &g, ld
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
-            float p[16], ds[16];
+            float p[8], ds[8];
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
+            for (int i2 = 0; i2 < 2; ++i2) {
+                const int kk = 2 * DH + i2;
                 const floatx4 l4 = *(lds_f32x4 *)(aux_lse + 8 * kk + 4 * X.h);
                 const floatx4 d4 = *(lds_f32x4 *)(aux_drow + 8 * kk + 4 * X.h);
                 const floatx4 i4 = *(lds_f32x4 *)(aux_i + 8 * kk + 4 * X.h);
 #pragma unroll
                 for (int t2 = 0; t2 < 4; ++t2) {
-                    const int e = 4 * kk + t2;
+                    const int e = 4 * i2 + t2;
                     // the row sees suffix key `key` iff key <= its position (and the key exists)
                     const bool vis = (float)key <= i4[t2] && key < len;
-                    p[e] = vis ? fast_exp2(__builtin_fmaf(s[e], X.c, -l4[t2])) : 0.f;
-                    ds[e] = p[e] * (dp[e] - d4[t2]);
+                    p[e] = vis ? fast_exp2(__builtin_fmaf(sf[e], X.c, -l4[t2])) : 0.f;
+                    ds[e] = p[e] * (dpf[e] - d4[t2]);
                 }
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             __builtin_amdgcn_wave_barrier();
-            bf16x8 pfp[2], pfs[2];
+            // this step's packed weights and score gradients go to the other wavefront, the other step's come back
+            uintx4 pfp_u[2], pfs_u[2];
+            pfp_u[DH] = uintx4{pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7])};
+            pfs_u[DH] = uintx4{pack_bf16(ds[0], ds[1]), pack_bf16(ds[2], ds[3]), pack_bf16(ds[4], ds[5]), pack_bf16(ds[6], ds[7])};
+            *(lds_u128 *)(xch_mine + 4096) = pfp_u[DH];
+            *(lds_u128 *)(xch_mine + 4096 + 1024) = pfs_u[DH];
+            __syncthreads(); // also: the other wavefront has read this block's sums before the next block's are written
+            pfp_u[1 - DH] = *(lds_u128 *)(xch_other + 4096);
+            pfs_u[1 - DH] = *(lds_u128 *)(xch_other + 4096 + 1024);
+            const bf16x8 pfp[2] = {as_bf16x8(pfp_u[0]), as_bf16x8(pfp_u[1])}, pfs[2] = {as_bf16x8(pfs_u[0]), as_bf16x8(pfs_u[1])};
+            // the second products: this half of the columns of dV^T and dK^T
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                pfp[j] = as_bf16x8(uintx4{pack_bf16(p[8 * j + 0], p[8 * j + 1]), pack_bf16(p[8 * j + 2], p[8 * j + 3]),
-                                          pack_bf16(p[8 * j + 4], p[8 * j + 5]), pack_bf16(p[8 * j + 6], p[8 * j + 7])});
-                pfs[j] = as_bf16x8(uintx4{pack_bf16(ds[8 * j + 0], ds[8 * j + 1]), pack_bf16(ds[8 * j + 2], ds[8 * j + 3]),
-                                          pack_bf16(ds[8 * j + 4], ds[8 * j + 5]), pack_bf16(ds[8 * j + 6], ds[8 * j + 7])});
-            }
-            // dO^T and Q^T of the block through the scratch tile, 16 rows at a time
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                pv_half_from_fragments<DH>(X, doh, j, pfp[j], dv);
-                pv_half_from_fragments<DH>(X, qh, j, pfs[j], dk);
-            }
-            __syncthreads(); // the other wavefront has read this block's halves before the next block's are written
+                for (int i2 = 0; i2 < 2; ++i2) {
+                    dv[i2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at[j][0][i2], pfp[j], dv[i2], 0, 0, 0);
+                    dk[i2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(at[j][1][i2], pfs[j], dk[i2], 0, 0, 0);
+                }
+            // The requests for the next block have had the whole block's work to land; waiting for them
+            // here, in so many words, keeps the compiler from waiting for them at the top of the loop,
+            // before the matrix instructions that do not need them (its bookkeeping of loads in flight
+            // across the loop's back edge is coarse).
+            if constexpr (kAhead)
+                __builtin_amdgcn_s_waitcnt(0x0F70); // vector memory counter at zero, the others untouched
+            // (No barrier here: what this wavefront writes next for the other one - the next block's sums - is
+            // read by it after the next barrier only, and it has read this block's before it reached the last one.)
         }
     }
     const bool kvalid = key < len;
+    // where this lane's rows of the gradients go (worked out here, not before the loop: no registers held across it)
+    unsigned short *dst_k[4], *dst_v[4];
+    bool dst_ok[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int jr = k0 + 8 * u + (X.lane >> 3);
+        dst_ok[u] = jr < a.S;
+        const long long off = (long long)b * a.ks_sb + (long long)(dst_ok[u] ? jr : 0) * a.ks_ss + (long long)k * a.ks_sh +
+                              8 * (X.lane & 7);
+        dst_k[u] = reinterpret_cast<unsigned short *>(g.dk) + off;
+        dst_v[u] = reinterpret_cast<unsigned short *>(g.dv) + off;
+    }
     // the store routine addresses accumulators by column group: hand it this half in its place
     const floatx16 dk4[4] = {dk[0], dk[1], dk[0], dk[1]}, dv4[4] = {dv[0], dv[1], dv[0], dv[1]};
     store_rows<DH, DH>(X, dst_k, dst_ok, kvalid, a.scale, dk4);
@@ -783,12 +814,19 @@ void bwd_dkv_mfma_kernel(BwdArgs g, int nkt)
     extern __shared__ __align__(16) unsigned char smem_generic[];
     lds_u8 *smem = (lds_u8 *)smem_generic;
     const int tid = threadIdx.x;
-    // one unit per workgroup, one half of the output columns per wavefront (wave-uniform branch; both sides
-    // meet the same workgroup barriers the same number of times)
+    // One unit - (candidate, KV head, 32-key tile) - per workgroup, one half of the output columns per
+    // wavefront.  Workgroup ids go round the XCDs: the tiles of one (candidate, KV head) pair take
+    // consecutive ids on ONE of them, so that they run there at the same time and share its L2.
+    const int x = blockIdx.x & 7, y = blockIdx.x >> 3;
+    const int grp = y / nkt, kt = y - grp * nkt;
+    const long long bk = (long long)grp * 8 + x;
+    if (bk >= (long long)g.f.B * g.f.Hkv) // the pairs are padded to a multiple of 8 (the same for the whole workgroup)
+        return;
+    // (wave-uniform branch; both sides meet the same workgroup barriers the same number of times)
     if (__builtin_amdgcn_readfirstlane(tid >> 6))
-        bwd_dkv_unit<1, HAS_DELTA>(g, smem, tid, blockIdx.x, nkt);
+        bwd_dkv_unit<1, HAS_DELTA>(g, smem, tid, (int)bk, kt);
     else
-        bwd_dkv_unit<0, HAS_DELTA>(g, smem, tid, blockIdx.x, nkt);
+        bwd_dkv_unit<0, HAS_DELTA>(g, smem, tid, (int)bk, kt);
 }
 
 } // namespace
@@ -802,7 +840,7 @@ hipError_t launch_bwd_dkv_mfma(const BwdArgs &g, hipStream_t stream)
 {
     const Args &a = g.f;
     const int nkt = (a.S + kTileKeys - 1) / kTileKeys;
-    const long long nunits = (long long)a.B * a.Hkv * nkt; // one workgroup each
+    const long long nunits = ((long long)a.B * a.Hkv + 7) / 8 * 8 * nkt; // one workgroup each; pairs padded to a multiple of 8
     if (nunits > 0x7fffffffLL)
         return hipErrorInvalidValue;
     if (g.delta)
