@@ -20,6 +20,7 @@
 // No running maximum is needed: lse comes from the forward pass, every weight is at most one.
 // A second kernel further down keeps short prefixes resident in LDS instead of streaming them.
 #include "pskv_mfma.hpp"
+#include <type_traits>
 
 // Scratch of the entry point that allocates nothing (pskv_attn_bwd_noalloc): <dout_row, out_row> of
 // every query row, B*Hq*S floats, handed from the dq kernel to the dk/dv kernel.  In host code this
@@ -214,7 +215,10 @@ void bwd_dq_mfma_kernel(BwdArgs g, int npasses)
                     }
                     const int nv = X.P - kt * kTileKeys - 4 * X.h; // element e holds key 8*(e/4) + e%4 + 4*h of the tile
                     bf16x8 pf[2];
-                    ds_tile(s, dp, X.c, lse2, drow, [&](int e) { return 8 * (e >> 2) + (e & 3) < nv; }, pf);
+                    if ((kt + 1) * kTileKeys <= X.P) // a full tile: every row sees all of it
+                        ds_tile(s, dp, X.c, lse2, drow, [](int) { return true; }, pf);
+                    else
+                        ds_tile(s, dp, X.c, lse2, drow, [&](int e) { return 8 * (e >> 2) + (e & 3) < nv; }, pf);
 #pragma unroll
                     for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -418,8 +422,8 @@ void bwd_dq_resident_kernel(BwdArgs g, int per_vh, int vh_slots, int max_tiles)
                 for (int e = 0; e < 16; ++e)
                     o[dt][e] = 0.f;
 
-            // ---- prefix part: every row sees every prefix key ----
-            for (int kt = 0; kt < T; ++kt) {
+            // ---- prefix part: every row sees every prefix key (only a ragged last tile has keys to hide) ----
+            auto prefix_tile = [&](int kt, auto ragged) {
                 const int to = kt * kTileBytes;
                 floatx16 s, dp;
 #pragma unroll
@@ -436,7 +440,10 @@ void bwd_dq_resident_kernel(BwdArgs g, int per_vh, int vh_slots, int max_tiles)
                 }
                 const int nv = X.P - kt * kTileKeys - 4 * X.h; // element e holds key 8*(e/4) + e%4 + 4*h of the tile
                 bf16x8 pf[2];
-                ds_tile(s, dp, X.c, lse2, drow, [&](int e) { return 8 * (e >> 2) + (e & 3) < nv; }, pf);
+                if constexpr (decltype(ragged)::value)
+                    ds_tile(s, dp, X.c, lse2, drow, [&](int e) { return 8 * (e >> 2) + (e & 3) < nv; }, pf);
+                else
+                    ds_tile(s, dp, X.c, lse2, drow, [](int) { return true; }, pf);
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -448,7 +455,12 @@ void bwd_dq_resident_kernel(BwdArgs g, int per_vh, int vh_slots, int max_tiles)
                         __builtin_memcpy(&kf, &v8, 16);
                         o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, pf[j], o[dt], 0, 0, 0);
                     }
-            }
+            };
+            const int Tfull = X.P / kTileKeys;
+            for (int kt = 0; kt < Tfull; ++kt)
+                prefix_tile(kt, std::false_type{});
+            if (Tfull < T)
+                prefix_tile(Tfull, std::true_type{});
 
             // ---- suffix part: 32-key steps of the block's own candidate ----
             {
