@@ -552,9 +552,9 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
     bool wg_bad = false, wg_short = false;
     int p = blockIdx.x;
     CandPass ps = make_cand_pass(a, cs, p, npasses, wave);
-    Row nxt = decode_row(a, X, ps.blk, ps.head, ps.cand0);
+    BlockRows nxt = decode_block(a, X, ps.blk, ps.head, ps.cand0);
     uintx4 q[8]; // this pass's Q fragments until their last use, then the next pass's
-    load_q(a, X, nxt, q);
+    load_q_block(a, X, nxt, q);
 
     while (p < npasses) {
         set_vhead(a, X, ps.vh);
@@ -566,11 +566,11 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
             if (!nothing)
                 wg_short = true; // prefix too short for the pipeline: left to the general sweep below
             else if (ps.active)
-                store_zero_block(a, X, ps.blk * kBlockRows, nxt);
+                store_zero_block_rows(a, X, nxt);
             p += gridDim.x;
             ps = make_cand_pass(a, cs, p, npasses, wave);
-            nxt = decode_row(a, X, ps.blk, ps.head, ps.cand0);
-            load_q(a, X, nxt, q);
+            nxt = decode_block(a, X, ps.blk, ps.head, ps.cand0);
+            load_q_block(a, X, nxt, q);
             continue;
         }
         const int i_hi = (int)fdiv(ps.cblk_last * kBlockRows + kBlockRows - 1, a.div_g);
@@ -589,8 +589,7 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
             g.ks = reinterpret_cast<const unsigned char *>(X.ksg + (long long)ps.b * a.ks_sb);
             g.vs = reinterpret_cast<const unsigned char *>(X.vsg + (long long)ps.b * a.ks_sb);
         }
-        const int r0 = ps.blk * kBlockRows;
-        const Row row = nxt;
+        const BlockRows row = nxt;
         // This wavefront's own share of the pass's tiles: the prefix and the suffix tiles up to the
         // last key its own block sees (Tw <= T); none at all if it has no block or its block holds
         // nothing but padding (then it only stores zeros).
@@ -599,7 +598,7 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
         const int i_hi_w = (int)fdiv(cblk * kBlockRows + kBlockRows - 1, a.div_g);
         const bool active = ps.active && i_lo_w < len;
         const int Tw = Tp + (i_hi_w < skmax ? i_hi_w : skmax) / kTileKeys + 1;
-        const bool rvalid = active && row.rin && (int)row.ri < clamp_len(a, row.rlen);
+        const bool rvalid = active && row.ri < row.len;
 
         // The ring is free here (the barrier that ended the previous pass).  Tiles 0..3 go in at once.
         uintx4 kv0, vv0, kv1, vv1;
@@ -622,7 +621,7 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
         // offset 8*(e/4) + e%4 + 4*h within the tile) is visible iff its offset without the
         // 4*h is <= lim.  Prefix tiles are fully visible but for the end of a ragged last one;
         // suffix tile j holds keys 32*j.. of which the row sees those up to its own position.
-        const int lim_suffix = (int)row.ri - 4 * X.h + Tp * kTileKeys;
+        const int lim_suffix = row.ri - 4 * X.h + Tp * kTileKeys;
         const int lim_last_prefix = X.P - (Tp - 1) * kTileKeys - 1 - 4 * X.h;
         auto lim_of = [&](int t) { return t >= Tp ? lim_suffix - t * kTileKeys : (t == Tp - 1 ? lim_last_prefix : 1 << 20); };
         const int tm = X.P / kTileKeys; // first tile with keys that some row does not see (>= 2)
@@ -632,7 +631,7 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
         // neighbour: same barriers, in the same order, as the path below.
         if (!active) {
             if (ps.active)
-                store_zero_block(a, X, r0, row);
+                store_zero_block_rows(a, X, row);
             for (int t = 2; t + 1 <= T - 2; t += 2) {
                 stage_write(t + 2, kv0, vv0);
                 stage_write(t + 3, kv1, vv1);
@@ -642,8 +641,8 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
             }
             p += gridDim.x;
             ps = make_cand_pass(a, cs, p, npasses, wave);
-            nxt = decode_row(a, X, ps.blk, ps.head, ps.cand0);
-            load_q(a, X, nxt, q);
+            nxt = decode_block(a, X, ps.blk, ps.head, ps.cand0);
+            load_q_block(a, X, nxt, q);
             if (X.lane == 0)
                 *(lds_int *)X.scr = 0;
             __syncthreads(); // ends the pass
@@ -719,8 +718,8 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
         // Q has been used for the last time: the next pass's Q takes its place
         p += gridDim.x;
         ps = make_cand_pass(a, cs, p, npasses, wave);
-        nxt = decode_row(a, X, ps.blk, ps.head, ps.cand0);
-        load_q(a, X, nxt, q);
+        nxt = decode_block(a, X, ps.blk, ps.head, ps.cand0);
+        load_q_block(a, X, nxt, q);
 
         // ---- last tile: its weights under the value product of the tile before, then its own ----
         pipe_tile<false, false, true, false, true, false, false>(kimg(0), nokf, vimg(Tw - 2), kimg(0), vimg(0), pre, q, sA, sA,
@@ -737,7 +736,7 @@ void stream_candidate_kernel(Args a, int npasses, CandShape cs)
             cand_stage_load(g, t + 5, kv1, vv1);
             __syncthreads();
         }
-        store_block(a, X, r0, row, rvalid, m, l, o);
+        store_block_rows(a, X, row, m, l, o);
         if (X.lane == 0)
             *(lds_int *)X.scr = bad ? 1 : 0;
         __syncthreads(); // ends the pass: the ring is free, the verdicts are visible
