@@ -82,15 +82,15 @@ def alg_counts(w, suf_len, pre_len=None):
 # kernel sources they were taken on (kernel_source_rev()).  When the sources have changed since, the
 # bench line reports no traffic and says why, instead of a figure that no longer holds.
 HBM_TRAFFIC = {
-    "gqa8b_bf16": {"file": "resident_pipelined_kernel_gqa8b_bf16_hbm_traffic.txt", "rev": "8c7521a516eb", "mfma_flops": 111887253504.0, "fetch_kib": 142208.0, "fetch_scale": 2.0, "write_kib": 197632.8, "write_scale": 1.0},
-    "ldec_gqa8b_bf16": {"file": "stream_candidate_kernel_ldec_gqa8b_bf16_hbm_traffic.txt", "rev": "8c7521a516eb", "mfma_flops": 134809124864.0, "fetch_kib": 238004.4, "fetch_scale": 2.0, "write_kib": 327680.2, "write_scale": 1.0},
-    "ldec_qwen7b_bf16": {"file": "stream_candidate_kernel_ldec_qwen7b_bf16_hbm_traffic.txt", "rev": "8c7521a516eb", "mfma_flops": 116735868928.0, "fetch_kib": 180886.7, "fetch_scale": 2.0, "write_kib": 286720.0, "write_scale": 1.0},
-    "longprefix_bf16": {"file": "stream_pipelined_kernel_longprefix_bf16_hbm_traffic.txt", "rev": "8c7521a516eb", "mfma_flops": 279172874240.0, "fetch_kib": 62930.4, "fetch_scale": 2.0, "write_kib": 66569.8, "write_scale": 1.0},
-    "mha13b_bf16": {"file": "stream_pipelined_kernel_mha13b_bf16_hbm_traffic.txt", "rev": "8c7521a516eb", "mfma_flops": 3004086353920.0, "fetch_kib": 3937667.2, "fetch_scale": 2.0, "write_kib": 2622464.0, "write_scale": 1.0},
-    "mha7b_bf16": {"file": "resident_general_kernel_mha7b_bf16_hbm_traffic.txt", "rev": "8c7521a516eb", "mfma_flops": 34359738368.0, "fetch_kib": 129183.0, "fetch_scale": 2.0, "write_kib": 81920.8, "write_scale": 1.0},
-    "multi32_gqa8b_bf16": {"file": "resident_pipelined_kernel_multi32_gqa8b_bf16_hbm_traffic.txt", "rev": "8c7521a516eb", "mfma_flops": 85198897152.0, "fetch_kib": 151814.5, "fetch_scale": 2.0, "write_kib": 197632.0, "write_scale": 1.0},
-    "multi4_long_bf16": {"file": "stream_pipelined_kernel_multi4_long_bf16_hbm_traffic.txt", "rev": "8c7521a516eb", "mfma_flops": 73014444032.0, "fetch_kib": 60179.9, "fetch_scale": 2.0, "write_kib": 66560.0, "write_scale": 1.0},
-    "multi8_gqa8b_bf16": {"file": "resident_pipelined_kernel_multi8_gqa8b_bf16_hbm_traffic.txt", "rev": "8c7521a516eb", "mfma_flops": 93021274112.0, "fetch_kib": 142292.6, "fetch_scale": 2.0, "write_kib": 197632.0, "write_scale": 1.0},
+    "gqa8b_bf16": {"file": "resident_pipelined_kernel_gqa8b_bf16_hbm_traffic.txt", "rev": "fb40c361063e", "mfma_flops": 111887253504.0, "fetch_kib": 145715.3, "fetch_scale": 2.0, "write_kib": 198657.2, "write_scale": 1.0},
+    "ldec_gqa8b_bf16": {"file": "stream_candidate_kernel_ldec_gqa8b_bf16_hbm_traffic.txt", "rev": "fb40c361063e", "mfma_flops": 134809124864.0, "fetch_kib": 221373.3, "fetch_scale": 2.0, "write_kib": 327680.1, "write_scale": 1.0},
+    "ldec_qwen7b_bf16": {"file": "stream_candidate_kernel_ldec_qwen7b_bf16_hbm_traffic.txt", "rev": "fb40c361063e", "mfma_flops": 116735868928.0, "fetch_kib": 166240.9, "fetch_scale": 2.0, "write_kib": 286720.0, "write_scale": 1.0},
+    "longprefix_bf16": {"file": "stream_pipelined_kernel_longprefix_bf16_hbm_traffic.txt", "rev": "fb40c361063e", "mfma_flops": 279172874240.0, "fetch_kib": 64018.0, "fetch_scale": 2.0, "write_kib": 67076.1, "write_scale": 1.0},
+    "mha13b_bf16": {"file": "stream_pipelined_kernel_mha13b_bf16_hbm_traffic.txt", "rev": "fb40c361063e", "mfma_flops": 3004086353920.0, "fetch_kib": 3417269.0, "fetch_scale": 2.0, "write_kib": 2624512.0, "write_scale": 1.0},
+    "mha7b_bf16": {"file": "resident_general_kernel_mha7b_bf16_hbm_traffic.txt", "rev": "fb40c361063e", "mfma_flops": 34359738368.0, "fetch_kib": 127336.6, "fetch_scale": 2.0, "write_kib": 81921.1, "write_scale": 1.0},
+    "multi32_gqa8b_bf16": {"file": "resident_pipelined_kernel_multi32_gqa8b_bf16_hbm_traffic.txt", "rev": "fb40c361063e", "mfma_flops": 85198897152.0, "fetch_kib": 154322.6, "fetch_scale": 2.0, "write_kib": 198656.0, "write_scale": 1.0},
+    "multi4_long_bf16": {"file": "stream_pipelined_kernel_multi4_long_bf16_hbm_traffic.txt", "rev": "fb40c361063e", "mfma_flops": 73014444032.0, "fetch_kib": 60927.7, "fetch_scale": 2.0, "write_kib": 67072.0, "write_scale": 1.0},
+    "multi8_gqa8b_bf16": {"file": "resident_pipelined_kernel_multi8_gqa8b_bf16_hbm_traffic.txt", "rev": "fb40c361063e", "mfma_flops": 93021274112.0, "fetch_kib": 145677.4, "fetch_scale": 2.0, "write_kib": 198656.0, "write_scale": 1.0},
 }
 
 
@@ -138,7 +138,7 @@ def cpu_baseline_multi(inp, budget_s=12.0):
 
 # The same for one backward call (its two kernels together).
 HBM_TRAFFIC_BWD = {
-    "gqa8b_bf16": {"file": "bwd_kernels_gqa8b_bf16_hbm_traffic.txt", "rev": "203f5e25f161", "mfma_flops": 192694714368.0, "fetch_kib": 510872.3, "fetch_scale": 2.0, "write_kib": 301673.8, "write_scale": 1.0},
+    "gqa8b_bf16": {"file": "bwd_kernels_gqa8b_bf16_hbm_traffic.txt", "rev": "8787530a226c", "mfma_flops": 192694714368.0, "fetch_kib": 510604.3, "fetch_scale": 2.0, "write_kib": 297560.1, "write_scale": 1.0},
 }
 
 
