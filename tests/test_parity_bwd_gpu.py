@@ -61,6 +61,10 @@ def test_bwd_tiny_f32(pk):
     (2, 700, 70, 33, 70, 2, 2),     # long suffix-side segment
     (3, 128, 160, 100, 160, 8, 2),  # the scoring workload in small: resident prefix, five suffix steps
     (2, 100, 96, 40, 96, 14, 2),    # the same with a query-head group of 7 and a ragged prefix tile
+    (3, 128, 160, 0, 160, 4, 1),    # passes cut out of one candidate: empty, short and full candidates
+    (3, 300, 40, 5, 40, 8, 2),      # ... one pass of 5 blocks per unit, streamed prefix
+    (9, 70, 64, 64, 64, 4, 1),      # ... more units than eight
+    (2, 0, 96, 1, 96, 4, 2),        # ... no prefix at all
 ])
 def test_bwd_small_shapes_bf16(pk, impl, B, P, S, lo, hi, Hq, Hkv):
     w = gen.custom_workload(f"bwd_{B}_{P}_{S}_{Hq}_{Hkv}", B, P, S, lo, hi, Hq, Hkv, 128, "bf16", index=800 + B + P)
