@@ -103,6 +103,38 @@ __device__ inline void ds_tile(const floatx16 &s, const floatx16 &dp, float c, f
     }
 }
 
+// O^T-style accumulation for the 16-key step j of a 32-key tile whose rows the lanes hold as
+// row-major fragments (lane (key c32, half h): columns 16*ks + 8*h ..+7 in frag[ks]): the lanes
+// that own keys of step j put their chunks where the scratch image wants them - chunk (key r,
+// columns 16*ks + 8*h) belongs to fragment (dt = ks/2, u = (r/8)%2), slot pair
+// 16*((r/4)%2) + 8*(ks%2) + 2*(r%4) + h - and the transposing reads hand them back as A
+// fragments (cf. pv_from_scratch, which takes the rows in image order from global memory).
+__device__ inline void pv_from_fragments(const Ctx &X, const uintx4 (&frag)[8], int j, bf16x8 pfj, floatx16 (&o)[4])
+{
+    if ((X.c32 >> 4) == j) {
+        const int u = (X.c32 >> 3) & 1;
+        lds_u8 *dst = X.scr + u * 512 + (16 * ((X.c32 >> 2) & 1) + 2 * (X.c32 & 3) + X.h) * 16;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+            *(lds_u128 *)(dst + (ks >> 1) * 1024 + (ks & 1) * 128) = frag[ks];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    bf16x8 va[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) {
+        short4v lo = lds_read_tr(X.scr + X.lane * 8 + (dt * 2 + 0) * 512);
+        short4v hi = lds_read_tr(X.scr + X.lane * 8 + (dt * 2 + 1) * 512);
+        short8v v8 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        __builtin_memcpy(&va[dt], &v8, 16);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[dt], pfj, o[dt], 0, 0, 0);
+}
+
 __global__ __attribute__((amdgpu_flat_work_group_size(512, 512), amdgpu_waves_per_eu(2, 2)))
 void bwd_dq_mfma_kernel(BwdArgs g, int npasses)
 {
@@ -234,9 +266,8 @@ void bwd_dq_mfma_kernel(BwdArgs g, int npasses)
 
         // ---- suffix part: (candidate, 32-key step) pairs, wave-uniform ----
         if (work) {
-            Ctx Xs = X; // K and V of the suffix trade places: V in row-major fragments, K through the scratch tile
+            Ctx Xs = X; // the suffix V rows are fetched as row-major fragments too: the K loader pointed at V
             Xs.ksg = X.vsg;
-            Xs.vsg = X.ksg;
             const int last_row = r0 + kBlockRows - 1 < X.Mtot ? r0 + kBlockRows - 1 : X.Mtot - 1;
             const int tok_first = fdiv(r0, a.div_g), tok_last = fdiv(last_row, a.div_g);
             const int bl_last = fdiv(tok_last, a.div_s);
@@ -255,13 +286,13 @@ void bwd_dq_mfma_kernel(BwdArgs g, int npasses)
                         s[e] = 0.f;
                         dp[e] = 0.f;
                     }
-                    {
-                        uintx4 kf[8];
-                        load_suffix_k(a, X, b, k0, kmax, kf);
+                    // K rows once, as row-major fragments: A operands of S^T here, and the source of the
+                    // transposed fragments of dQ^T further down
+                    uintx4 kf[8];
+                    load_suffix_k(a, X, b, k0, kmax, kf);
 #pragma unroll
-                        for (int ks = 0; ks < 8; ++ks)
-                            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[ks]), as_bf16x8(q[ks]), s, 0, 0, 0);
-                    }
+                    for (int ks = 0; ks < 8; ++ks)
+                        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[ks]), as_bf16x8(q[ks]), s, 0, 0, 0);
                     {
                         uintx4 vf[8];
                         load_suffix_k(a, Xs, b, k0, kmax, vf); // V rows as row-major fragments
@@ -269,14 +300,12 @@ void bwd_dq_mfma_kernel(BwdArgs g, int npasses)
                         for (int ks = 0; ks < 8; ++ks)
                             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vf[ks]), as_bf16x8(dof[ks]), dp, 0, 0, 0);
                     }
-                    uintx4 ktf[2][4];
-                    load_suffix_v(a, Xs, b, k0, kmax, ktf); // K rows in scratch-image order
                     // the row sees keys 0..ri of its own candidate; element e holds key k0 + 8*(e/4) + e%4 + 4*h
                     const int lim = ((int)row.rb == b ? (int)row.ri : -1) - k0 - 4 * X.h;
                     bf16x8 pf[2];
                     ds_tile(s, dp, X.c, lse2, drow, [&](int e) { return 8 * (e >> 2) + (e & 3) <= lim; }, pf);
-                    pv_from_scratch(X, ktf[0], pf[0], o);
-                    pv_from_scratch(X, ktf[1], pf[1], o);
+                    pv_from_fragments(X, kf, 0, pf[0], o);
+                    pv_from_fragments(X, kf, 1, pf[1], o);
                 }
             }
         }
@@ -464,9 +493,8 @@ void bwd_dq_resident_kernel(BwdArgs g, int per_vh, int vh_slots, int max_tiles)
 
             // ---- suffix part: 32-key steps of the block's own candidate ----
             {
-                Ctx Xs = X; // K and V of the suffix trade places: V in row-major fragments, K through the scratch tile
+                Ctx Xs = X; // the suffix V rows are fetched as row-major fragments too: the K loader pointed at V
                 Xs.ksg = X.vsg;
-                Xs.vsg = X.ksg;
                 for (int k0 = 0; k0 <= kmax; k0 += kTileKeys) {
                     floatx16 s, dp;
 #pragma unroll
@@ -474,13 +502,13 @@ void bwd_dq_resident_kernel(BwdArgs g, int per_vh, int vh_slots, int max_tiles)
                         s[e] = 0.f;
                         dp[e] = 0.f;
                     }
-                    {
-                        uintx4 kf[8];
-                        load_suffix_k_block(a, X, row.b, k0, kmax, kf);
+                    // K rows once, as row-major fragments: A operands of S^T here, and the source of the
+                    // transposed fragments of dQ^T further down
+                    uintx4 kf[8];
+                    load_suffix_k_block(a, X, row.b, k0, kmax, kf);
 #pragma unroll
-                        for (int ks = 0; ks < 8; ++ks)
-                            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[ks]), as_bf16x8(q[ks]), s, 0, 0, 0);
-                    }
+                    for (int ks = 0; ks < 8; ++ks)
+                        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(kf[ks]), as_bf16x8(q[ks]), s, 0, 0, 0);
                     {
                         uintx4 vf[8];
                         load_suffix_k_block(a, Xs, row.b, k0, kmax, vf); // V rows as row-major fragments
@@ -488,14 +516,12 @@ void bwd_dq_resident_kernel(BwdArgs g, int per_vh, int vh_slots, int max_tiles)
                         for (int ks = 0; ks < 8; ++ks)
                             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vf[ks]), as_bf16x8(dof[ks]), dp, 0, 0, 0);
                     }
-                    uintx4 ktf[2][4];
-                    load_suffix_v_block(a, Xs, row.b, k0, kmax, ktf); // K rows in scratch-image order
                     // the row sees keys 0..ri of its candidate; element e holds key k0 + 8*(e/4) + e%4 + 4*h
                     const int lim = row.ri - k0 - 4 * X.h;
                     bf16x8 pf[2];
                     ds_tile(s, dp, X.c, lse2, drow, [&](int e) { return 8 * (e >> 2) + (e & 3) <= lim; }, pf);
-                    pv_from_scratch(X, ktf[0], pf[0], o);
-                    pv_from_scratch(X, ktf[1], pf[1], o);
+                    pv_from_fragments(X, kf, 0, pf[0], o);
+                    pv_from_fragments(X, kf, 1, pf[1], o);
                 }
             }
             // store_block_rows divides by the sum of both half-waves' l: 1/(2 * 0.5/scale) = scale
