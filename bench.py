@@ -138,10 +138,10 @@ def cpu_baseline_multi(inp, budget_s=12.0):
 
 # The same for one backward call (its two kernels together).
 HBM_TRAFFIC_BWD = {
-    "gqa8b_bf16": {"file": "bwd_kernels_gqa8b_bf16_hbm_traffic.txt", "rev": "8787530a226c", "mfma_flops": 192694714368.0, "fetch_kib": 510604.3, "fetch_scale": 2.0, "write_kib": 297560.1, "write_scale": 1.0},
-    "ldec_gqa8b_bf16": {"file": "bwd_kernels_ldec_gqa8b_bf16_hbm_traffic.txt", "rev": "8787530a226c", "mfma_flops": 313824116736.0, "fetch_kib": 1111831.3, "fetch_scale": 2.0, "write_kib": 496137.0, "write_scale": 1.0},
-    "longprefix_bf16": {"file": "bwd_kernels_longprefix_bf16_hbm_traffic.txt", "rev": "8787530a226c", "mfma_flops": 427349245952.0, "fetch_kib": 226771.9, "fetch_scale": 2.0, "write_kib": 99384.6, "write_scale": 1.0},
-    "mha7b_bf16": {"file": "bwd_kernels_mha7b_bf16_hbm_traffic.txt", "rev": "8787530a226c", "mfma_flops": 68719476736.0, "fetch_kib": 381956.7, "fetch_scale": 2.0, "write_kib": 247394.0, "write_scale": 1.0},
+    "gqa8b_bf16": {"file": "bwd_kernels_gqa8b_bf16_hbm_traffic.txt", "rev": "88d93c09003d", "mfma_flops": 192694714368.0, "fetch_kib": 510434.3, "fetch_scale": 2.0, "write_kib": 297552.0, "write_scale": 1.0},
+    "ldec_gqa8b_bf16": {"file": "bwd_kernels_ldec_gqa8b_bf16_hbm_traffic.txt", "rev": "88d93c09003d", "mfma_flops": 313824116736.0, "fetch_kib": 1110306.6, "fetch_scale": 2.0, "write_kib": 496137.0, "write_scale": 1.0},
+    "longprefix_bf16": {"file": "bwd_kernels_longprefix_bf16_hbm_traffic.txt", "rev": "88d93c09003d", "mfma_flops": 427349245952.0, "fetch_kib": 214788.7, "fetch_scale": 2.0, "write_kib": 99372.3, "write_scale": 1.0},
+    "mha7b_bf16": {"file": "bwd_kernels_mha7b_bf16_hbm_traffic.txt", "rev": "88d93c09003d", "mfma_flops": 68719476736.0, "fetch_kib": 380369.3, "fetch_scale": 2.0, "write_kib": 247379.0, "write_scale": 1.0},
 }
 
 
