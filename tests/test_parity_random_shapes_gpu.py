@@ -62,6 +62,47 @@ def test_random_shape(pk, case):
         print("      ", name, pu.compare_grad(pu.out_to_f64(got), r, valid, "bf16", f"{w.name} {name}"), flush=True)
 
 
+def draw_long_suffix_shape(case: int):
+    """Suffix-side segments of four to seven key tiles (suffix, template tail and target together):
+    the shapes that take the passes cut out of one candidate, or the streamed kernels' multi-step
+    suffix, depending on the query-head group."""
+    rng = np.random.default_rng(2977 + case)
+    G = int(rng.choice([1, 2, 4, 7, 8]))
+    Hkv = int(rng.choice([1, 2, 4]))
+    P = int(rng.choice([0, rng.integers(1, 96), rng.integers(96, 257), rng.integers(257, 900)]))
+    S = int(rng.choice([8 * rng.integers(13, 26), 32 * rng.integers(3, 7)]))
+    B = int(rng.integers(1, 10))
+    lo = int(rng.integers(0, S + 1))
+    return B, P, S, lo, S, G * Hkv, Hkv
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_random_long_suffix_shape(pk, case):
+    import torch
+    B, P, S, lo, hi, Hq, Hkv = draw_long_suffix_shape(case)
+    w = gen.custom_workload(f"randlong{case}", B, P, S, lo, hi, Hq, Hkv, 128, "bf16", index=1400 + case)
+    inp = gen.make_inputs(w, pad="nan")
+    d = pu.to_device(inp)
+    print(f"[case] random long-suffix shape {case}: B={B} P={P} S={S} len={lo}..{hi} Hq={Hq} Hkv={Hkv} seed={w.seed}", flush=True)
+    lse = torch.full((B, Hq, S), 123.0, device="cuda:0")
+    out = torch.full_like(d["q"], float("nan"))
+    pk.pskv_attn_fwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], out=out, lse=lse,
+                     scale=inp.scale)
+    torch.cuda.synchronize()
+    ref, ref_lse = pu.oracle_out(inp, want_lse=True)
+    pu.compare_lse(lse.cpu().numpy().astype(np.float64), ref_lse, inp.suf_len, "bf16", w.name)
+    print("      ", pu.compare(pu.out_to_f64(out), ref, inp.suf_len, "bf16", w.name), flush=True)
+    dout_host, dout64 = pu.make_dout(inp, w.seed + 7)
+    dout = torch.from_numpy(dout_host).view(torch.bfloat16).to("cuda:0")
+    dq, dk, dv = pk.pskv_attn_bwd(d["q"], d["k_suf"], d["v_suf"], d["k_pre"], d["v_pre"], d["suf_len"], out, lse, dout,
+                                  scale=inp.scale)
+    torch.cuda.synchronize()
+    rq, rk, rv = pu.oracle_bwd(inp, dout64)
+    valid = np.arange(S)[None, :] < inp.suf_len[:, None]
+    for name, got, r in (("dq", dq, rq), ("dk_suf", dk, rk), ("dv_suf", dv, rv)):
+        print("      ", name, pu.compare_grad(pu.out_to_f64(got), r, valid, "bf16", f"{w.name} {name}"), flush=True)
+
+
 def draw_multi_shape(case: int):
     rng = np.random.default_rng(1977 + case)
     G = int(rng.choice([1, 2, 4, 7]))
