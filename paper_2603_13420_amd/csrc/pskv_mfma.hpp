@@ -623,6 +623,89 @@ __device__ inline void suffix_step_fixed(const Ctx &X, int ri, int k0, const flo
     pv_from_scratch(X, svf[1], as_bf16x8(uintx4{pk[4], pk[5], pk[6], pk[7]}), o);
 }
 
+// ------------------------------------------------------------------------------------------
+// Passes of the streamed forward kernels.
+// ------------------------------------------------------------------------------------------
+// A pass is one (virtual head, group of 256 stacked rows) pair; a virtual head is one
+// (instruction, KV head) pair with its own prefix and its own C*S*G stacked rows.
+//
+// Pass ids are laid out for the L2 caches.  All (virtual head, group) pairs, head by head, form one
+// list of items - the heads in the order 0, 8, 16, ..., 1, 9, 17, ..., so that neighbours in the
+// list belong to different instructions of the multi-instruction form, whose prefixes differ in
+// length, and every stretch of the list is a fair sample of them; the workgroups whose ids are x modulo 8 - one XCD, ids going round the XCDs -
+// take pass ids p = 8*y + x, y = 0, 1, ..., 32 at a time, and what matters is which items those
+// are.  (With items dealt out head by head, item = p, each XCD cycled through five heads of the
+// 13B-shaped workload at once and one prefix request in eight went to memory.)
+//   - Heads of fewer than 256 groups: XCD x takes the x-th eighth of the list, in order.  It
+//     works on one head at a time and a head's prefix is fetched into one L2, two at a boundary.
+//   - Longer heads: the list is cut into chunks of 32 items and XCD x takes the chunks x, x+8, ...
+//     The whole chip then works on one head at a time, each XCD on its own 32 groups of it
+//     (measured 4 % faster on the 13B-shaped workload than XCDs that own heads).
+// Either way every XCD gets the same number of items to within one chunk; the ids past the end
+// of the list hold nothing.
+struct Pass {
+    int vh, head, cand0; // virtual head = instruction * Hkv + KV head; first candidate of the instruction
+    int blk;             // this wavefront's block (clamped to the last one)
+    bool exists;         // the pass id holds an item (the same for the whole workgroup)
+    bool active;         // ... and this wavefront's block exists
+};
+
+constexpr int kChunk = 32;           // items per chunk: the compute units of an XCD
+constexpr int kLongHead = 8 * kChunk; // groups per head from which the chunked order is used
+
+// Items per XCD in the first order, rounds times 32 in the second: pass ids = 8 * this.
+__host__ __device__ inline long long pass_ids_per_xcd(long long items, long long ngroups)
+{
+    return ngroups < kLongHead ? (items + 7) / 8 : (items + 8 * kChunk - 1) / (8 * kChunk) * kChunk;
+}
+
+// (The launchers see to it that the pass ids, and with them the items, fit 31 bits.)
+__device__ inline Pass make_pass(const Args &a, int p, int npasses, int nblocks, int wave)
+{
+    Pass ps;
+    const int pc = p < npasses ? p : npasses - 1;
+    const int VH = a.Np * a.Hkv;
+    const int ngroups = (nblocks + kNW - 1) / kNW;
+    const int items = VH * ngroups;
+    const int x = pc & 7, y = pc >> 3;
+    int item;
+    bool in_list;
+    if (ngroups < kLongHead) {
+        const int per = (items + 7) >> 3;
+        item = x * per + y;
+        in_list = y < per && item < items;
+    } else {
+        item = ((y / kChunk) * 8 + x) * kChunk + y % kChunk;
+        in_list = item < items;
+    }
+    ps.exists = p < npasses && in_list;
+    item = in_list ? item : items - 1;
+    const int hpos = item / ngroups; // place of the head in the list
+    const int group = item - hpos * ngroups;
+    {
+        const int nfull = VH >> 3, rem = VH & 7; // residue r modulo 8 has nfull + (r < rem) heads
+        const int cut = rem * (nfull + 1);
+        const int r = hpos < cut ? hpos / (nfull + 1) : rem + (hpos - cut) / (nfull > 0 ? nfull : 1);
+        const int k = hpos < cut ? hpos - r * (nfull + 1) : (hpos - cut) - (r - rem) * nfull;
+        ps.vh = k * 8 + r;
+    }
+    const int n = ps.vh / a.Hkv;
+    ps.head = ps.vh - n * a.Hkv;
+    ps.cand0 = n * a.C;
+    const int blk = group * kNW + wave;
+    ps.active = ps.exists && blk < nblocks;
+    ps.blk = blk < nblocks ? blk : nblocks - 1;
+    return ps;
+}
+
+// Pass ids of the streamed kernels (see make_pass).
+inline long long stream_pass_ids(const Args &a)
+{
+    const long long rows = (long long)a.C * a.S * a.G;
+    const long long ngroups = ((rows + kBlockRows - 1) / kBlockRows + kNW - 1) / kNW;
+    return 8 * pass_ids_per_xcd((long long)a.Np * a.Hkv * ngroups, ngroups);
+}
+
 // Fragments 0 and 1 of the images a pipeline step starts with, read during the step before.
 constexpr int kDist = 2; // LDS fragments are read this many sub-steps before their use
 struct Pre {

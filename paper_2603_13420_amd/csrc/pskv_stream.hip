@@ -10,9 +10,8 @@
 // candidates) from L2 straight into a small ring of fragment-major LDS images while the current
 // tiles are being used, and meet at one barrier per two tiles.  Every tile is thus
 // read once per 256 rows, whatever candidates those rows belong to, and the prefix itself is
-// read from HBM once: consecutive workgroup ids (one per XCD in turn) take passes of
-// consecutive heads, so the workgroups of one XCD keep returning to the same few heads and
-// find them in that XCD's L2.
+// read from HBM about once per XCD: pass ids are laid out so that the workgroups of one XCD
+// (workgroup ids go round the XCDs) work on one head at a time, and find it in that XCD's L2.
 //
 // Three kernels.  The pipelined one (every 32-row block inside one candidate) is the software
 // pipeline of the resident-prefix kernel with the tile images taken from the ring, the suffix
@@ -34,29 +33,6 @@ constexpr int kPassRows = kNW * kBlockRows;
 constexpr int kMinTiles = 3;                // shortest prefix, in tiles, that the pipelined pass takes
 
 typedef __attribute__((address_space(3))) int lds_int;
-
-// A pass is one (virtual head, group of 256 stacked rows) pair; a virtual head is one
-// (instruction, KV head) pair with its own prefix and its own C*S*G stacked rows.
-struct Pass {
-    int vh, head, cand0; // virtual head = instruction * Hkv + KV head; first candidate of the instruction
-    int blk;             // this wavefront's block (clamped to the last one)
-    bool active;         // the block exists
-};
-
-__device__ inline Pass make_pass(const Args &a, int p, int npasses, int nblocks, int wave)
-{
-    Pass ps;
-    const int pc = p < npasses ? p : npasses - 1;
-    const int VH = a.Np * a.Hkv;
-    ps.vh = pc % VH;
-    const int n = ps.vh / a.Hkv;
-    ps.head = ps.vh - n * a.Hkv;
-    ps.cand0 = n * a.C;
-    const int blk = (pc / VH) * kNW + wave;
-    ps.active = p < npasses && blk < nblocks;
-    ps.blk = blk < nblocks ? blk : nblocks - 1;
-    return ps;
-}
 
 __device__ inline Ctx make_stream_ctx(const Args &a, lds_u8 *smem, int tid)
 {
@@ -141,7 +117,8 @@ void stream_general_kernel(Args a, int npasses)
     const int nblocks = (X.Mtot + kBlockRows - 1) / kBlockRows;
     for (int p = blockIdx.x; p < npasses; p += gridDim.x) {
         const Pass ps = make_pass(a, p, npasses, nblocks, wave);
-        general_pass(a, X, smem, tid, ps.vh, ps.blk, ps.active);
+        if (ps.exists)
+            general_pass(a, X, smem, tid, ps.vh, ps.blk, ps.active);
     }
 }
 
@@ -229,8 +206,9 @@ void stream_pipelined_kernel(Args a, int npasses)
     while (p < npasses) {
         set_vhead(a, X, ps.vh);
         const int T = (X.P + kTileKeys - 1) / kTileKeys;
-        if (T < kMinTiles) { // this instruction's prefix is too short for the pipeline: left to the general sweep below
-            wg_short = true;
+        if (!ps.exists || T < kMinTiles) { // nothing here, or this instruction's prefix is too short for the pipeline:
+                                           // left to the general sweep below
+            wg_short |= ps.exists;
             p += gridDim.x;
             ps = make_pass(a, p, npasses, nblocks, wave);
             nxt = decode_block(a, X, ps.blk, ps.head, ps.cand0);
@@ -418,7 +396,7 @@ void stream_pipelined_kernel(Args a, int npasses)
         for (int p2 = blockIdx.x; p2 < npasses; p2 += gridDim.x) {
             const Pass ps2 = make_pass(a, p2, npasses, nblocks, wave);
             set_vhead(a, X, ps2.vh);
-            if (wg_bad || (X.P + kTileKeys - 1) / kTileKeys < kMinTiles)
+            if (ps2.exists && (wg_bad || (X.P + kTileKeys - 1) / kTileKeys < kMinTiles))
                 general_pass(a, X, smem, tid, ps2.vh, ps2.blk, ps2.active);
         }
 }
@@ -780,8 +758,7 @@ bool mfma_supported(const Args &a, int dtype)
     if (dtype != 1 || a.D != kD)
         return false;
     const long long rows = (long long)a.C * a.S * a.G;
-    const long long passes = ((rows + kPassRows - 1) / kPassRows) * a.Np * a.Hkv;
-    return rows <= 0x7fffffffLL - kPassRows && passes <= 0x7fffffffLL;
+    return rows <= 0x7fffffffLL - kPassRows && stream_pass_ids(a) <= 0x7fffffffLL - 8;
 }
 
 hipError_t launch_mfma(const Args &a, hipStream_t stream)
@@ -803,8 +780,7 @@ hipError_t launch_stream(const Args &a, hipStream_t stream)
     if (e != hipSuccess)
         return e;
     const int max_tiles = (a.P + kTileKeys - 1) / kTileKeys;
-    const long long rows = (long long)a.C * a.S * a.G; // stacked rows of one virtual head
-    const long long npasses = ((rows + kPassRows - 1) / kPassRows) * a.Np * a.Hkv;
+    const long long npasses = stream_pass_ids(a);
     const unsigned grid = (unsigned)(npasses < num_cu ? npasses : num_cu);
     const bool pipelined = ((long long)a.S * a.G) % kBlockRows == 0 && max_tiles >= kMinTiles &&
                            (long long)a.P * a.kp_sp * 2 < 0x7fffffffLL && block_offsets_fit(a);
