@@ -82,15 +82,15 @@ def alg_counts(w, suf_len, pre_len=None):
 # kernel sources they were taken on (kernel_source_rev()).  When the sources have changed since, the
 # bench line reports no traffic and says why, instead of a figure that no longer holds.
 HBM_TRAFFIC = {
-    "gqa8b_bf16": {"file": "resident_pipelined_kernel_gqa8b_bf16_hbm_traffic.txt", "rev": "fb40c361063e", "mfma_flops": 111887253504.0, "fetch_kib": 145715.3, "fetch_scale": 2.0, "write_kib": 198657.2, "write_scale": 1.0},
-    "ldec_gqa8b_bf16": {"file": "stream_candidate_kernel_ldec_gqa8b_bf16_hbm_traffic.txt", "rev": "fb40c361063e", "mfma_flops": 134809124864.0, "fetch_kib": 221373.3, "fetch_scale": 2.0, "write_kib": 327680.1, "write_scale": 1.0},
-    "ldec_qwen7b_bf16": {"file": "stream_candidate_kernel_ldec_qwen7b_bf16_hbm_traffic.txt", "rev": "fb40c361063e", "mfma_flops": 116735868928.0, "fetch_kib": 166240.9, "fetch_scale": 2.0, "write_kib": 286720.0, "write_scale": 1.0},
-    "longprefix_bf16": {"file": "stream_pipelined_kernel_longprefix_bf16_hbm_traffic.txt", "rev": "fb40c361063e", "mfma_flops": 279172874240.0, "fetch_kib": 64018.0, "fetch_scale": 2.0, "write_kib": 67076.1, "write_scale": 1.0},
-    "mha13b_bf16": {"file": "stream_pipelined_kernel_mha13b_bf16_hbm_traffic.txt", "rev": "fb40c361063e", "mfma_flops": 3004086353920.0, "fetch_kib": 3417269.0, "fetch_scale": 2.0, "write_kib": 2624512.0, "write_scale": 1.0},
-    "mha7b_bf16": {"file": "resident_general_kernel_mha7b_bf16_hbm_traffic.txt", "rev": "fb40c361063e", "mfma_flops": 34359738368.0, "fetch_kib": 127336.6, "fetch_scale": 2.0, "write_kib": 81921.1, "write_scale": 1.0},
-    "multi32_gqa8b_bf16": {"file": "resident_pipelined_kernel_multi32_gqa8b_bf16_hbm_traffic.txt", "rev": "fb40c361063e", "mfma_flops": 85198897152.0, "fetch_kib": 154322.6, "fetch_scale": 2.0, "write_kib": 198656.0, "write_scale": 1.0},
-    "multi4_long_bf16": {"file": "stream_pipelined_kernel_multi4_long_bf16_hbm_traffic.txt", "rev": "fb40c361063e", "mfma_flops": 73014444032.0, "fetch_kib": 60927.7, "fetch_scale": 2.0, "write_kib": 67072.0, "write_scale": 1.0},
-    "multi8_gqa8b_bf16": {"file": "resident_pipelined_kernel_multi8_gqa8b_bf16_hbm_traffic.txt", "rev": "fb40c361063e", "mfma_flops": 93021274112.0, "fetch_kib": 145677.4, "fetch_scale": 2.0, "write_kib": 198656.0, "write_scale": 1.0},
+    "gqa8b_bf16": {"file": "resident_pipelined_kernel_gqa8b_bf16_hbm_traffic.txt", "rev": "030ab9797c1d", "mfma_flops": 111887253504.0, "fetch_kib": 141986.1, "fetch_scale": 2.0, "write_kib": 197632.1, "write_scale": 1.0},
+    "ldec_gqa8b_bf16": {"file": "stream_candidate_kernel_ldec_gqa8b_bf16_hbm_traffic.txt", "rev": "030ab9797c1d", "mfma_flops": 134809124864.0, "fetch_kib": 221361.0, "fetch_scale": 2.0, "write_kib": 327680.0, "write_scale": 1.0},
+    "ldec_qwen7b_bf16": {"file": "stream_candidate_kernel_ldec_qwen7b_bf16_hbm_traffic.txt", "rev": "030ab9797c1d", "mfma_flops": 116735868928.0, "fetch_kib": 166274.9, "fetch_scale": 2.0, "write_kib": 286720.0, "write_scale": 1.0},
+    "longprefix_bf16": {"file": "stream_pipelined_kernel_longprefix_bf16_hbm_traffic.txt", "rev": "030ab9797c1d", "mfma_flops": 279172874240.0, "fetch_kib": 63776.4, "fetch_scale": 2.0, "write_kib": 66566.6, "write_scale": 1.0},
+    "mha13b_bf16": {"file": "stream_pipelined_kernel_mha13b_bf16_hbm_traffic.txt", "rev": "030ab9797c1d", "mfma_flops": 3004086353920.0, "fetch_kib": 3170597.3, "fetch_scale": 2.0, "write_kib": 2625024.2, "write_scale": 1.0},
+    "mha7b_bf16": {"file": "resident_general_kernel_mha7b_bf16_hbm_traffic.txt", "rev": "030ab9797c1d", "mfma_flops": 34359738368.0, "fetch_kib": 129098.4, "fetch_scale": 2.0, "write_kib": 81921.1, "write_scale": 1.0},
+    "multi32_gqa8b_bf16": {"file": "resident_pipelined_kernel_multi32_gqa8b_bf16_hbm_traffic.txt", "rev": "030ab9797c1d", "mfma_flops": 85198897152.0, "fetch_kib": 151851.1, "fetch_scale": 2.0, "write_kib": 197632.0, "write_scale": 1.0},
+    "multi4_long_bf16": {"file": "stream_pipelined_kernel_multi4_long_bf16_hbm_traffic.txt", "rev": "030ab9797c1d", "mfma_flops": 73014444032.0, "fetch_kib": 53888.5, "fetch_scale": 2.0, "write_kib": 66596.2, "write_scale": 1.0},
+    "multi8_gqa8b_bf16": {"file": "resident_pipelined_kernel_multi8_gqa8b_bf16_hbm_traffic.txt", "rev": "030ab9797c1d", "mfma_flops": 93021274112.0, "fetch_kib": 142354.0, "fetch_scale": 2.0, "write_kib": 197632.0, "write_scale": 1.0},
 }
 
 
@@ -138,10 +138,10 @@ def cpu_baseline_multi(inp, budget_s=12.0):
 
 # The same for one backward call (its two kernels together).
 HBM_TRAFFIC_BWD = {
-    "gqa8b_bf16": {"file": "bwd_kernels_gqa8b_bf16_hbm_traffic.txt", "rev": "88d93c09003d", "mfma_flops": 192694714368.0, "fetch_kib": 510434.3, "fetch_scale": 2.0, "write_kib": 297552.0, "write_scale": 1.0},
-    "ldec_gqa8b_bf16": {"file": "bwd_kernels_ldec_gqa8b_bf16_hbm_traffic.txt", "rev": "88d93c09003d", "mfma_flops": 313824116736.0, "fetch_kib": 1110306.6, "fetch_scale": 2.0, "write_kib": 496137.0, "write_scale": 1.0},
-    "longprefix_bf16": {"file": "bwd_kernels_longprefix_bf16_hbm_traffic.txt", "rev": "88d93c09003d", "mfma_flops": 427349245952.0, "fetch_kib": 214788.7, "fetch_scale": 2.0, "write_kib": 99372.3, "write_scale": 1.0},
-    "mha7b_bf16": {"file": "bwd_kernels_mha7b_bf16_hbm_traffic.txt", "rev": "88d93c09003d", "mfma_flops": 68719476736.0, "fetch_kib": 380369.3, "fetch_scale": 2.0, "write_kib": 247379.0, "write_scale": 1.0},
+    "gqa8b_bf16": {"file": "bwd_kernels_gqa8b_bf16_hbm_traffic.txt", "rev": "545ee1bf5fd1", "mfma_flops": 192694714368.0, "fetch_kib": 510429.4, "fetch_scale": 2.0, "write_kib": 297554.9, "write_scale": 1.0},
+    "ldec_gqa8b_bf16": {"file": "bwd_kernels_ldec_gqa8b_bf16_hbm_traffic.txt", "rev": "545ee1bf5fd1", "mfma_flops": 313824116736.0, "fetch_kib": 1109511.1, "fetch_scale": 2.0, "write_kib": 496137.0, "write_scale": 1.0},
+    "longprefix_bf16": {"file": "bwd_kernels_longprefix_bf16_hbm_traffic.txt", "rev": "545ee1bf5fd1", "mfma_flops": 427349245952.0, "fetch_kib": 214787.5, "fetch_scale": 2.0, "write_kib": 99366.5, "write_scale": 1.0},
+    "mha7b_bf16": {"file": "bwd_kernels_mha7b_bf16_hbm_traffic.txt", "rev": "545ee1bf5fd1", "mfma_flops": 68719476736.0, "fetch_kib": 380369.0, "fetch_scale": 2.0, "write_kib": 247379.1, "write_scale": 1.0},
 }
 
 
